@@ -1,0 +1,174 @@
+/*
+ * alpa_dp.h — C ABI of the MI355X (gfx950) stage-slicing dynamic program.
+ *
+ * The library solves the inter-operator planning problem of Sec. 5.1-5.2:
+ * cut K layers into contiguous pipeline stages, give every stage one submesh
+ * shape out of a fixed family so that the device counts add up to N*M, and
+ * minimise   sum_i t_i + (B - 1) * max_j t_j   (Eq. 2)   by enumerating the
+ * bound t_max, minimising the latency sum under "every stage <= t_max" with
+ * the recurrence F(s, k, d; t_max) (Eq. 3) and adding (B - 1) * t_max (Eq. 4),
+ * as in the dynamic-programming loop of Alg. 1.  Every step runs in HIP
+ * kernels on the device the handle was created on; there is no CPU fallback.
+ *
+ * Conventions
+ *   - latencies are int32 microseconds, >= 0; INT32_MAX means +infinity
+ *     (stage does not fit in memory, Eq. 5); sums and T* are int64;
+ *   - layers are 0-based at this boundary; a stage is [first, last];
+ *   - the third table index s is "number of stages from this stage to the last
+ *     one, inclusive" (the s of Eq. 3), 1 <= s <= K;
+ *   - tie-breaks are fixed so that results are unique: inside Eq. 3 the lowest
+ *     last layer, then the lowest shape index; in Eq. 4 the lowest s; over
+ *     candidates the lowest t_max;
+ *   - the filter of Eq. 3 is  t_intra <= t_max.
+ *
+ * All functions return ALPA_DP_OK (0) or a negative error code and never throw
+ * or abort; alpa_dp_last_error() gives a message for the calling thread's last
+ * failure.  An infeasible problem is not an error (T_star = ALPA_DP_INF_I64,
+ * num_stages = 0).  A handle may be used by one thread at a time; distinct
+ * handles are independent.
+ */
+#ifndef ALPA_DP_H
+#define ALPA_DP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ALPA_DP_MAX_K        256          /* most layers                         */
+#define ALPA_DP_MAX_DEVICES  1024         /* largest N*M                         */
+#define ALPA_DP_MAX_SHAPES   64           /* most submesh shapes                 */
+#define ALPA_DP_INF_I32      INT32_MAX    /* +infinity in cost_table             */
+#define ALPA_DP_INF_I64      INT64_MAX    /* infeasible / not evaluated T*       */
+
+#define ALPA_DP_OK            0
+#define ALPA_DP_EINVAL       (-1)         /* bad argument                        */
+#define ALPA_DP_EOVERFLOW    (-2)         /* K * max finite latency >= 2^30      */
+#define ALPA_DP_ENOMEM       (-3)         /* host or device allocation failed    */
+#define ALPA_DP_EHIP         (-4)         /* a HIP call failed                   */
+
+/* flags of alpa_dp_solve / alpa_dp_solve_dev */
+#define ALPA_DP_PRUNE         1u          /* early pruning of Alg. 1 / Sec. 5.2 opt. #1 */
+#define ALPA_DP_COUNT_WORK    4u          /* tally executed work (alpa_dp_last_counters) */
+#define ALPA_DP_GENERIC       2u          /* use the general kernel even where the
+                                             K <= 64, N*M <= 64 kernel applies   */
+
+typedef struct alpa_dp alpa_dp_t;         /* opaque, owned by the library        */
+
+typedef struct { int32_t n, m; } alpa_shape_t;   /* submesh of n x m devices    */
+
+typedef struct {
+    int64_t T_star;                       /* Eq. 2 value; ALPA_DP_INF_I64 if none      */
+    int32_t t_max;                        /* winning candidate (us); 0 if none         */
+    int32_t num_stages;                   /* stages of the plan; 0 if none             */
+    int32_t n_evaluated;                  /* candidates processed before the pruning
+                                             break (= number of distinct candidates
+                                             when pruning is off)                      */
+    int32_t first_layer[ALPA_DP_MAX_K + 1]; /* stage p (pipeline order) holds layers
+                                             [first_layer[p], first_layer[p+1])        */
+    int32_t shape_idx[ALPA_DP_MAX_K];     /* index into shapes[] for stage p           */
+} alpa_plan_t;
+
+/*
+ * Problem statement of Sec. 5.1 (operators o_1..o_K, cluster mesh N x M, B
+ * microbatches) plus the t_intra table of Sec. 5.2 / Alg. 1 ("costs of different
+ * stage-mesh pairs").
+ *
+ *   cost_table  HOST pointer, read during the call only (the library keeps its own
+ *               device copies in the layouts its kernels want).  C order
+ *               [s-1][k][i][q], extents K x K x K x num_shapes; k / i = first / last
+ *               layer of the stage; entries with i < k are ignored.
+ *   shapes      HOST pointer, read during the call only.  Every shape must belong to
+ *               the family of Sec. 5.2: (1, 2^p) with 2^p <= M, or (n, M) with
+ *               2 <= n <= N; M must be a power of two (Appendix A).  The order
+ *               defines the shape index used in tie-breaks; duplicates are allowed.
+ *   *out        receives the handle; destroy with alpa_dp_destroy.
+ *
+ * Errors: EINVAL (null pointer, K < 1 or > ALPA_DP_MAX_K, N*M > ALPA_DP_MAX_DEVICES,
+ * B < 1, num_shapes < 1 or > ALPA_DP_MAX_SHAPES, shape outside the family, negative
+ * latency), EOVERFLOW (K * largest finite latency >= 2^30: the kernels add in int32),
+ * ENOMEM, EHIP.  The device is the calling thread's current HIP device; work is
+ * queued on the null stream until alpa_dp_set_stream is called.
+ */
+int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table,
+                   int K, int N, int M, int B,
+                   const alpa_shape_t *shapes, int num_shapes);
+
+/* Queue all later work of this handle on `hip_stream` (a hipStream_t; e.g. the
+ * cuda_stream field of a torch.cuda.Stream).  The caller keeps the stream alive. */
+int alpa_dp_set_stream(alpa_dp_t *h, void *hip_stream);
+
+/* Change B (Sec. 7: B is a hyper-parameter searched by enumeration).  B >= 1. */
+int alpa_dp_set_B(alpa_dp_t *h, int B);
+
+/* Number of distinct finite values of the table (entries with i >= k): the length
+ * of Alg. 1's "SortedAndFilter(t_intra, epsilon)" list for integer latencies and
+ * epsilon = 1 us.  Computed on the device at create time. */
+int alpa_dp_count_candidates(alpa_dp_t *h, int *out_n);
+
+/*
+ * The dynamic-programming loop of Alg. 1 over a list of t_max candidates, blocking.
+ *
+ *   tmax     HOST pointer to n_tmax candidates in any order, duplicates allowed
+ *            (sorted and deduplicated on the device), each in [0, INT32_MAX); or NULL:
+ *            then the candidates are the distinct finite table values, ascending —
+ *            all of them if n_tmax == 0, else n_tmax evenly spaced quantiles
+ *            v[(j * (n - 1)) / (n_tmax - 1)] (all if there are no more than n_tmax;
+ *            n_tmax >= 2).
+ *   flags    ALPA_DP_PRUNE: stop at the first candidate (ascending) with
+ *            B * t_max >= best T* so far, exactly as the sequential loop would; the
+ *            remaining candidates report ALPA_DP_INF_I64.
+ *   out_T    HOST pointer or NULL.  tmax != NULL: n_tmax values, out_T[j] = T*(tmax[j])
+ *            of Eq. 4 in the caller's order (duplicates get equal values).
+ *            tmax == NULL: one value per candidate in ascending candidate order
+ *            (alpa_dp_count_candidates() values, or min(that, n_tmax)).
+ *   out_plan HOST pointer or NULL: best plan of this call.
+ *
+ * Errors: EINVAL (null handle, n_tmax < 0, n_tmax == 0 with tmax != NULL, n_tmax == 1
+ * with tmax == NULL, candidate out of range), ENOMEM, EHIP.
+ */
+int alpa_dp_solve(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
+                  int64_t *out_T, alpa_plan_t *out_plan);
+
+/*
+ * Same computation with DEVICE pointers, asynchronous on the handle's stream: nothing
+ * is copied to or from the host and the call returns once the work is queued.
+ * d_tmax (or NULL), d_out_T (or NULL) and d_out_plan (or NULL) are device pointers
+ * with the sizes given for alpa_dp_solve; they must stay valid until the stream has
+ * run the work.  Candidates are not range-checked (values outside [0, INT32_MAX) give
+ * T* = ALPA_DP_INF_I64 or unfiltered results for that candidate, never a fault).
+ */
+int alpa_dp_solve_dev(alpa_dp_t *h, const int32_t *d_tmax, int n_tmax, unsigned flags,
+                      int64_t *d_out_T, alpa_plan_t *d_out_plan);
+
+/* Ascending distinct candidate list of the last solve on this handle: copies at most
+ * `cap` values to the HOST array `out` and stores the count in *out_n.  Blocking. */
+int alpa_dp_candidates(alpa_dp_t *h, int32_t *out, int cap, int *out_n);
+
+/* Best plan over every solve made on the handle so far (lowest T*, then lowest t_max);
+ * if none was made, runs alpa_dp_solve(h, NULL, 0, ALPA_DP_PRUNE, NULL, out_plan)
+ * first ("the minimal pipeline execution latency T*" that Alg. 1 outputs).  Blocking. */
+int alpa_dp_best(alpa_dp_t *h, alpa_plan_t *out_plan);
+
+/* Device time of the phases of the last solve, from HIP events recorded on the
+ * handle's stream: candidate preparation (sort / dedup / quantiles), the recurrence
+ * kernel of Eq. 3, and Eq. 4 + best selection + plan recovery.  Blocking.  Any
+ * pointer may be NULL. */
+int alpa_dp_last_timing(alpa_dp_t *h, float *ms_candidates, float *ms_recurrence,
+                        float *ms_epilogue);
+
+/* Counters of the last solve: number of distinct candidates, and the number of
+ * wave-level relaxation instructions' worth of work the recurrence kernel issued
+ * (64-lane add+min pairs), for the benchmark's executed-work figure.  Blocking. */
+int alpa_dp_last_counters(alpa_dp_t *h, int *n_candidates, int64_t *wave_relaxations);
+
+void alpa_dp_destroy(alpa_dp_t *h);
+
+/* Message of the calling thread's last failed call ("" if none).  Never NULL. */
+const char *alpa_dp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALPA_DP_H */

@@ -1,0 +1,454 @@
+// C ABI of libalpa_dp: argument checks, device buffers, and the order in which the
+// kernels of one solve are queued.  All arithmetic of the method is in the kernels.
+#include "../../include/alpa_dp.h"
+#include "internal.hpp"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace alpa;
+
+static_assert(sizeof(alpa_plan_t) == 2072, "plan layout differs from the kernels' PlanDev");
+
+static thread_local std::string g_err;
+
+static int fail(int code, const std::string &msg)
+{
+    g_err = msg;
+    return code;
+}
+
+#define HIPCHK(expr)                                                                        \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(e_ == hipErrorOutOfMemory ? ALPA_DP_ENOMEM : ALPA_DP_EHIP,          \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                 \
+    } while (0)
+
+struct alpa_dp {
+    Problem p{};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int32_t max_finite = -1;        // largest finite table entry with last >= first layer
+    int key_bits_table = 1;
+    int n_table_keys = 0;           // K * K(K+1)/2 * S
+    int n_distinct = 0;             // distinct finite table values
+    int n_cu = 0;
+    bool fast_ok = false;
+    int KP = 0;
+    int fast_grid_max = 0, generic_grid_max = 0;
+
+    int32_t *d_table = nullptr, *d_sizes = nullptr, *d_tfast = nullptr, *d_blkmm = nullptr;
+    PrepBuffers pb{};
+    int32_t *d_distinct = nullptr;
+    uint32_t *d_ncount = nullptr;   // [2]: distinct table values, distinct caller candidates
+    int32_t *d_cand = nullptr, *d_rank = nullptr, *d_tmax_stage = nullptr;
+    int32_t *d_Fmin = nullptr, *d_Sbest = nullptr;
+    int64_t *d_T = nullptr, *d_outT_stage = nullptr, *d_chunkmin = nullptr;
+    int cand_cap = 0;               // capacity of the per-candidate arrays
+    SolveState *d_state = nullptr;
+    int32_t *d_scratch = nullptr, *d_Fall = nullptr, *d_tmpFS = nullptr;
+    alpa_plan_t *d_plan_tmp = nullptr, *d_best_plan = nullptr;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool any_solve = false, timed = false;
+    int last_host_n = 0;
+};
+
+static void free_candidate_arrays(alpa_dp *h)
+{
+    (void)hipFree(h->pb.keys[0]); (void)hipFree(h->pb.keys[1]); (void)hipFree(h->pb.block_cnt);
+    (void)hipFree(h->d_cand); (void)hipFree(h->d_rank); (void)hipFree(h->d_tmax_stage);
+    (void)hipFree(h->d_Fmin); (void)hipFree(h->d_Sbest); (void)hipFree(h->d_T); (void)hipFree(h->d_outT_stage);
+    (void)hipFree(h->d_chunkmin); (void)hipFree(h->d_distinct);
+    h->pb.keys[0] = h->pb.keys[1] = nullptr; h->pb.block_cnt = nullptr;
+    h->d_cand = h->d_rank = h->d_tmax_stage = h->d_Fmin = h->d_Sbest = h->d_distinct = nullptr;
+    h->d_T = h->d_outT_stage = h->d_chunkmin = nullptr;
+    h->cand_cap = 0;
+}
+
+// Per-candidate arrays for up to `cap` keys / candidates.
+static int alloc_candidate_arrays(alpa_dp *h, int cap)
+{
+    free_candidate_arrays(h);
+    const size_t c = (size_t)cap;
+    HIPCHK(hipMalloc(&h->pb.keys[0], c * 4));
+    HIPCHK(hipMalloc(&h->pb.keys[1], c * 4));
+    HIPCHK(hipMalloc(&h->pb.block_cnt, (c / 4096 + 2) * 4));
+    HIPCHK(hipMalloc(&h->d_distinct, c * 4));
+    HIPCHK(hipMalloc(&h->d_cand, c * 4));
+    HIPCHK(hipMalloc(&h->d_rank, c * 4));
+    HIPCHK(hipMalloc(&h->d_tmax_stage, c * 4));
+    HIPCHK(hipMalloc(&h->d_Fmin, c * 4));
+    HIPCHK(hipMalloc(&h->d_Sbest, c * 4));
+    HIPCHK(hipMalloc(&h->d_T, c * 8));
+    HIPCHK(hipMalloc(&h->d_outT_stage, c * 8));
+    HIPCHK(hipMalloc(&h->d_chunkmin, (c / PRUNE_CHUNK + 2) * 8));
+    h->pb.cap = cap;
+    h->cand_cap = cap;
+    return ALPA_DP_OK;
+}
+
+static int bits_for(uint32_t v)
+{
+    int b = 1;
+    while (b < 32 && (v >> b)) ++b;
+    return b;
+}
+
+// distinct finite table values -> d_distinct, count -> d_ncount[0]
+static int queue_table_candidates(alpa_dp *h)
+{
+    const int32_t inf_key = h->max_finite + 1;
+    HIPCHK(launch_gather_table_values(h->stream, h->d_table, h->p.K, h->p.S, inf_key,
+                                      h->pb.keys[0]));
+    HIPCHK(launch_sort_dedup(h->stream, h->pb, h->n_table_keys, h->key_bits_table, inf_key,
+                             h->d_distinct, h->d_ncount + 0));
+    return ALPA_DP_OK;
+}
+
+extern "C" const char *alpa_dp_last_error(void) { return g_err.c_str(); }
+
+extern "C" void alpa_dp_destroy(alpa_dp_t *h)
+{
+    if (!h) return;
+    int prev = 0;
+    (void)hipGetDevice(&prev);
+    (void)hipSetDevice(h->device);
+    (void)hipStreamSynchronize(h->stream);
+    free_candidate_arrays(h);
+    (void)hipFree(h->d_table); (void)hipFree(h->d_sizes); (void)hipFree(h->d_tfast); (void)hipFree(h->d_blkmm);
+    (void)hipFree(h->pb.hist); (void)hipFree(h->d_ncount); (void)hipFree(h->d_state); (void)hipFree(h->d_scratch);
+    (void)hipFree(h->d_Fall); (void)hipFree(h->d_tmpFS); (void)hipFree(h->d_plan_tmp); (void)hipFree(h->d_best_plan);
+    for (auto &e : h->ev) if (e) (void)hipEventDestroy(e);
+    (void)hipSetDevice(prev);
+    delete h;
+}
+
+extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K, int N, int M,
+                              int B, const alpa_shape_t *shapes, int num_shapes)
+{
+    if (!out) return fail(ALPA_DP_EINVAL, "out is null");
+    *out = nullptr;
+    if (!cost_table || !shapes) return fail(ALPA_DP_EINVAL, "cost_table or shapes is null");
+    if (K < 1 || K > ALPA_DP_MAX_K) return fail(ALPA_DP_EINVAL, "K out of range");
+    if (N < 1 || M < 1 || (long long)N * M > ALPA_DP_MAX_DEVICES)
+        return fail(ALPA_DP_EINVAL, "N x M out of range");
+    if ((M & (M - 1)) != 0) return fail(ALPA_DP_EINVAL, "M must be a power of two");
+    if (B < 1) return fail(ALPA_DP_EINVAL, "B must be >= 1");
+    if (num_shapes < 1 || num_shapes > ALPA_DP_MAX_SHAPES)
+        return fail(ALPA_DP_EINVAL, "num_shapes out of range");
+    std::vector<int32_t> sizes(num_shapes);
+    for (int q = 0; q < num_shapes; ++q) {
+        const int n = shapes[q].n, m = shapes[q].m;
+        const bool one_d = n == 1 && m >= 1 && m <= M && (m & (m - 1)) == 0;
+        const bool two_d = m == M && n >= 2 && n <= N;
+        if (!one_d && !two_d) return fail(ALPA_DP_EINVAL, "shape outside the submesh family");
+        sizes[q] = n * m;
+    }
+    const int S = num_shapes, D = N * M;
+    // range check of the part of the table that is used
+    int32_t max_finite = -1;
+    for (int s = 0; s < K; ++s)
+        for (int k = 0; k < K; ++k) {
+            const int32_t *row = cost_table + (((size_t)s * K + k) * K + k) * S;
+            const size_t cnt = (size_t)(K - k) * S;
+            for (size_t x = 0; x < cnt; ++x) {
+                const int32_t t = row[x];
+                if (t < 0) return fail(ALPA_DP_EINVAL, "negative latency in cost_table");
+                if (t != ALPA_DP_INF_I32 && t > max_finite) max_finite = t;
+            }
+        }
+    if (max_finite >= 0 && (long long)K * max_finite >= (1ll << 30))
+        return fail(ALPA_DP_EOVERFLOW, "K * largest finite latency >= 2^30");
+
+    alpa_dp *h = new (std::nothrow) alpa_dp();
+    if (!h) return fail(ALPA_DP_ENOMEM, "host allocation failed");
+    h->p = Problem{K, N, M, D, S, std::min(K, D), B};
+    h->max_finite = max_finite;
+    h->key_bits_table = bits_for((uint32_t)(max_finite + 1));
+    h->n_table_keys = K * (K * (K + 1) / 2) * S;
+    int rc = ALPA_DP_OK;
+    auto body = [&]() -> int {
+        HIPCHK(hipGetDevice(&h->device));
+        hipDeviceProp_t prop;
+        HIPCHK(hipGetDeviceProperties(&prop, h->device));
+        h->n_cu = prop.multiProcessorCount;
+        for (auto &e : h->ev) HIPCHK(hipEventCreate(&e));
+        const size_t tbytes = (size_t)K * K * K * S * 4;
+        HIPCHK(hipMalloc(&h->d_table, tbytes));
+        HIPCHK(hipMemcpyAsync(h->d_table, cost_table, tbytes, hipMemcpyHostToDevice, h->stream));
+        HIPCHK(hipMalloc(&h->d_sizes, (size_t)S * 4));
+        HIPCHK(hipMemcpyAsync(h->d_sizes, sizes.data(), (size_t)S * 4, hipMemcpyHostToDevice,
+                              h->stream));
+        HIPCHK(hipMalloc(&h->pb.hist, 256 * 256 * 4));
+        HIPCHK(hipMalloc(&h->d_ncount, 2 * 4));
+        HIPCHK(hipMalloc(&h->d_state, sizeof(SolveState)));
+        HIPCHK(hipMemsetAsync(h->d_state, 0, sizeof(SolveState), h->stream));
+        HIPCHK(hipMalloc(&h->d_tmpFS, 2 * 4));
+        HIPCHK(hipMalloc(&h->d_plan_tmp, sizeof(alpa_plan_t)));
+        HIPCHK(hipMalloc(&h->d_best_plan, sizeof(alpa_plan_t)));
+        HIPCHK(launch_init_best_plan(h->stream, h->d_best_plan));
+        const size_t LS = (size_t)(K + 2) * (D + 1);
+        HIPCHK(hipMalloc(&h->d_Fall, (size_t)(h->p.Smax + 1) * LS * 4));
+        // general kernel: two F layers per resident workgroup, at most 256 MiB in total
+        int gg = h->n_cu * 4;
+        while (gg > 1 && (size_t)gg * 2 * LS * 4 > (256ull << 20)) gg /= 2;
+        h->generic_grid_max = gg;
+        HIPCHK(hipMalloc(&h->d_scratch, (size_t)gg * 2 * LS * 4));
+        // register/LDS kernel
+        h->fast_ok = K <= 64 && D <= 64;
+        if (h->fast_ok) {
+            h->KP = 16 * ((K + 15) / 16);
+            HIPCHK(hipMalloc(&h->d_tfast, (size_t)K * K * S * h->KP * 4));
+            HIPCHK(hipMalloc(&h->d_blkmm, (size_t)K * K * S * 8 * 4));
+            HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_tfast, h->d_blkmm));
+            const int per_cu = fast_kernel_blocks_per_cu(K);
+            if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
+            h->fast_grid_max = h->n_cu * per_cu;
+        }
+        int rc2 = alloc_candidate_arrays(h, std::max(h->n_table_keys, 1024));
+        if (rc2) return rc2;
+        // length of the full candidate list
+        rc2 = queue_table_candidates(h);
+        if (rc2) return rc2;
+        uint32_t nd = 0;
+        HIPCHK(hipMemcpyAsync(&nd, h->d_ncount, 4, hipMemcpyDeviceToHost, h->stream));
+        HIPCHK(hipStreamSynchronize(h->stream));
+        h->n_distinct = (int)nd;
+        return ALPA_DP_OK;
+    };
+    rc = body();
+    if (rc != ALPA_DP_OK) {
+        std::string keep = g_err;
+        alpa_dp_destroy(h);
+        g_err = keep;
+        return rc;
+    }
+    *out = h;
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_set_stream(alpa_dp_t *h, void *hip_stream)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    HIPCHK(hipStreamSynchronize(h->stream));
+    h->stream = (hipStream_t)hip_stream;
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_set_B(alpa_dp_t *h, int B)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    if (B < 1) return fail(ALPA_DP_EINVAL, "B must be >= 1");
+    h->p.B = B;
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_count_candidates(alpa_dp_t *h, int *out_n)
+{
+    if (!h || !out_n) return fail(ALPA_DP_EINVAL, "null argument");
+    *out_n = h->n_distinct;
+    return ALPA_DP_OK;
+}
+
+// Upper bound, known on the host, of the number of distinct candidates of a solve.
+static int candidate_bound(const alpa_dp *h, bool have_list, int n_tmax)
+{
+    if (have_list) return n_tmax;
+    if (n_tmax == 0) return h->n_distinct;
+    return std::min(h->n_distinct, n_tmax);
+}
+
+static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigned flags,
+                          int64_t *d_out_T, alpa_plan_t *d_out_plan, int key_bits)
+{
+    const Problem &p = h->p;
+    const bool have_list = d_tmax != nullptr;
+    if (n_tmax < 0) return fail(ALPA_DP_EINVAL, "n_tmax < 0");
+    if (have_list && n_tmax == 0) return fail(ALPA_DP_EINVAL, "empty candidate list");
+    if (!have_list && n_tmax == 1) return fail(ALPA_DP_EINVAL, "fewer than two quantiles");
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    if (have_list && n_tmax > h->cand_cap) {
+        HIPCHK(hipStreamSynchronize(h->stream));
+        int rc = alloc_candidate_arrays(h, n_tmax);
+        if (rc) return rc;
+    }
+    const int bound = candidate_bound(h, have_list, n_tmax);
+    const int prune = (flags & ALPA_DP_PRUNE) ? 1 : 0;
+    hipStream_t st = h->stream;
+
+    HIPCHK(hipEventRecord(h->ev[0], st));
+    HIPCHK(launch_init_state(st, h->d_state, h->d_chunkmin, bound / PRUNE_CHUNK + 1));
+    if (have_list) {
+        HIPCHK(hipMemcpyAsync(h->pb.keys[0], d_tmax, (size_t)n_tmax * 4, hipMemcpyDeviceToDevice,
+                              st));
+        HIPCHK(launch_sort_dedup(st, h->pb, n_tmax, key_bits, /*drop_key=*/-1, h->d_cand,
+                                 h->d_ncount + 1));
+        HIPCHK(launch_set_candidates(st, h->d_ncount + 1, h->d_state));
+        if (d_out_T)
+            HIPCHK(launch_rank_lookup(st, d_tmax, n_tmax, h->d_cand, h->d_ncount + 1, h->d_rank));
+    } else {
+        int rc = queue_table_candidates(h);
+        if (rc) return rc;
+        HIPCHK(launch_pick_candidates(st, h->d_distinct, h->d_ncount + 0, n_tmax, h->d_cand,
+                                      h->d_state, h->cand_cap));
+    }
+    HIPCHK(hipEventRecord(h->ev[1], st));
+    if (bound > 0) {
+        const bool fast = h->fast_ok && !(flags & ALPA_DP_GENERIC);
+        if (fast) {
+            const int grid = std::max(1, std::min(bound, h->fast_grid_max));
+            HIPCHK(launch_recurrence_fast(st, p, h->d_tfast, h->d_blkmm, h->d_sizes, h->d_cand,
+                                          h->d_state, h->d_chunkmin, prune,
+                                          /*count_work=*/(flags & ALPA_DP_COUNT_WORK) ? 1 : 0,
+                                          /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest,
+                                          grid));
+        } else {
+            const int grid = std::max(1, std::min(bound, h->generic_grid_max));
+            HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, h->d_cand,
+                                             &h->d_state->n_cand, &h->d_state->ticket,
+                                             h->d_chunkmin, prune, h->d_Fmin, h->d_Sbest,
+                                             h->d_scratch, 2, grid));
+        }
+    }
+    HIPCHK(hipEventRecord(h->ev[2], st));
+    HIPCHK(launch_epilogue(st, p, h->d_cand, h->d_Fmin, h->d_Sbest, h->d_state, prune, h->d_T));
+    if (d_out_T && bound > 0)
+        HIPCHK(launch_scatter_T(st, h->d_T, have_list ? h->d_rank : nullptr,
+                                have_list ? n_tmax : bound, h->d_state, d_out_T));
+    HIPCHK(launch_plan(st, p, h->d_table, h->d_sizes, h->d_state, h->d_Fall, h->d_tmpFS,
+                       h->d_plan_tmp, h->d_best_plan, d_out_plan));
+    HIPCHK(hipEventRecord(h->ev[3], st));
+    h->any_solve = true;
+    h->timed = true;
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_solve_dev(alpa_dp_t *h, const int32_t *d_tmax, int n_tmax, unsigned flags,
+                                 int64_t *d_out_T, alpa_plan_t *d_out_plan)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    return solve_dev_impl(h, d_tmax, n_tmax, flags, d_out_T, d_out_plan, 31);
+}
+
+extern "C" int alpa_dp_solve(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
+                             int64_t *out_T, alpa_plan_t *out_plan)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    if (n_tmax < 0) return fail(ALPA_DP_EINVAL, "n_tmax < 0");
+    int key_bits = 31;
+    const int32_t *d_tmax = nullptr;
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    if (tmax) {
+        if (n_tmax == 0) return fail(ALPA_DP_EINVAL, "empty candidate list");
+        int32_t mx = 0;
+        for (int j = 0; j < n_tmax; ++j) {
+            if (tmax[j] < 0 || tmax[j] == ALPA_DP_INF_I32)
+                return fail(ALPA_DP_EINVAL, "candidate out of range");
+            mx = std::max(mx, tmax[j]);
+        }
+        key_bits = bits_for((uint32_t)mx);
+        if (n_tmax > h->cand_cap) {
+            HIPCHK(hipStreamSynchronize(h->stream));
+            int rc = alloc_candidate_arrays(h, n_tmax);
+            if (rc) return rc;
+        }
+        HIPCHK(hipMemcpyAsync(h->d_tmax_stage, tmax, (size_t)n_tmax * 4, hipMemcpyHostToDevice,
+                              h->stream));
+        d_tmax = h->d_tmax_stage;
+    }
+    const int n_out = candidate_bound(h, tmax != nullptr, n_tmax);
+    int rc = solve_dev_impl(h, d_tmax, n_tmax, flags, out_T ? h->d_outT_stage : nullptr,
+                            out_plan ? h->d_plan_tmp : nullptr, key_bits);
+    if (rc) return rc;
+    if (out_T && n_out > 0)
+        HIPCHK(hipMemcpyAsync(out_T, h->d_outT_stage, (size_t)n_out * 8, hipMemcpyDeviceToHost,
+                              h->stream));
+    if (out_plan)
+        HIPCHK(hipMemcpyAsync(out_plan, h->d_plan_tmp, sizeof(alpa_plan_t), hipMemcpyDeviceToHost,
+                              h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    if (out_plan && out_plan->num_stages < 0)
+        return fail(ALPA_DP_EHIP, "internal inconsistency during plan recovery");
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_candidates(alpa_dp_t *h, int32_t *out, int cap, int *out_n)
+{
+    if (!h || !out_n || (cap > 0 && !out)) return fail(ALPA_DP_EINVAL, "null argument");
+    if (!h->any_solve) return fail(ALPA_DP_EINVAL, "no solve has been made on this handle");
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    SolveState s;
+    HIPCHK(hipMemcpyAsync(&s, h->d_state, sizeof(s), hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    *out_n = s.n_cand;
+    const int n = std::min(cap, s.n_cand);
+    if (n > 0) {
+        HIPCHK(hipMemcpyAsync(out, h->d_cand, (size_t)n * 4, hipMemcpyDeviceToHost, h->stream));
+        HIPCHK(hipStreamSynchronize(h->stream));
+    }
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_best(alpa_dp_t *h, alpa_plan_t *out_plan)
+{
+    if (!h || !out_plan) return fail(ALPA_DP_EINVAL, "null argument");
+    if (!h->any_solve) {
+        int rc = alpa_dp_solve(h, nullptr, 0, ALPA_DP_PRUNE, nullptr, nullptr);
+        if (rc) return rc;
+    }
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    HIPCHK(hipMemcpyAsync(out_plan, h->d_best_plan, sizeof(alpa_plan_t), hipMemcpyDeviceToHost,
+                          h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_last_timing(alpa_dp_t *h, float *ms_candidates, float *ms_recurrence,
+                                   float *ms_epilogue)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    if (!h->timed) return fail(ALPA_DP_EINVAL, "no solve has been made on this handle");
+    HIPCHK(hipEventSynchronize(h->ev[3]));
+    float a = 0, b = 0, c = 0;
+    HIPCHK(hipEventElapsedTime(&a, h->ev[0], h->ev[1]));
+    HIPCHK(hipEventElapsedTime(&b, h->ev[1], h->ev[2]));
+    HIPCHK(hipEventElapsedTime(&c, h->ev[2], h->ev[3]));
+    if (ms_candidates) *ms_candidates = a;
+    if (ms_recurrence) *ms_recurrence = b;
+    if (ms_epilogue) *ms_epilogue = c;
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_last_counters(alpa_dp_t *h, int *n_candidates, int64_t *wave_relaxations)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    if (!h->any_solve) return fail(ALPA_DP_EINVAL, "no solve has been made on this handle");
+    SolveState s;
+    HIPCHK(hipMemcpyAsync(&s, h->d_state, sizeof(s), hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    if (n_candidates) *n_candidates = s.n_cand;
+    if (wave_relaxations) *wave_relaxations = (int64_t)s.wave_relax;
+    return ALPA_DP_OK;
+}

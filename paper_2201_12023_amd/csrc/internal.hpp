@@ -1,0 +1,154 @@
+// Internal declarations shared by the translation units of libalpa_dp (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace alpa {
+
+// Device-side +infinity.  Finite sums stay below it (checked at create: K * max finite
+// latency < 2^30) and INF + INF = 2^31 - 2 still fits in int32, so "never add to
+// infinity" becomes "add, then anything >= DEV_INF is infinity".
+constexpr int32_t DEV_INF = (1 << 30) - 1;
+constexpr int64_t INF_I64 = INT64_MAX;
+constexpr int32_t INF_I32 = INT32_MAX;
+
+constexpr int WAVE = 64;
+constexpr int PRUNE_CHUNK = 64;          // candidates per published running-minimum slot
+
+// Result block of one solve, in device memory.
+struct SolveState {
+    int32_t n_cand;          // distinct candidates of this solve
+    int32_t ticket;          // next candidate index to hand out (recurrence kernel)
+    int32_t n_processed;     // prefix length after the exact pruning rule
+    int32_t best_idx;        // index of the winning candidate, -1 if none
+    int64_t best_T;          // its T*
+    int32_t best_c;          // its t_max
+    int32_t best_s;          // its number of stages
+    unsigned long long wave_relax;   // executed 64-lane relaxations (instrumented runs)
+    int32_t n_distinct;      // distinct finite table values seen by candidate preparation
+    int32_t plan_n;          // 1 if a plan is to be recovered (a feasible winner exists)
+    int32_t plan_ticket;     // ticket counter of the plan-recovery run
+    int32_t pad;
+};
+
+struct Problem {
+    int K, N, M, D, S, Smax, B;
+};
+
+// ---- wave-level reductions (DPP inside rows of 16, ds_swizzle across 16, bpermute across 32)
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+
+// xor-16 inside each half of the wave: ds_swizzle bit mode (and 0x1f, or 0, xor 0x10)
+__device__ __forceinline__ int swz_xor16(int v)
+{
+    return __builtin_amdgcn_ds_swizzle(v, 0x401F);
+}
+
+__device__ __forceinline__ int xor32(int v)
+{
+    return __shfl_xor(v, 32, 64);
+}
+
+// min over the 64 lanes, result in every lane
+__device__ __forceinline__ int wave_min_i32(int v)
+{
+    v = min(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = min(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = min(v, dpp_mov<0x141>(v));   // row_half_mirror
+    v = min(v, dpp_mov<0x140>(v));   // row_mirror
+    v = min(v, swz_xor16(v));
+    v = min(v, xor32(v));
+    return v;
+}
+
+__device__ __forceinline__ int64_t i64_from(int lo, int hi)
+{
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+__device__ __forceinline__ int lo32(int64_t v) { return (int)(uint32_t)(uint64_t)v; }
+__device__ __forceinline__ int hi32(int64_t v) { return (int)((uint64_t)v >> 32); }
+
+template <int CTRL>
+__device__ __forceinline__ int64_t dpp_mov64(int64_t v)
+{
+    return i64_from(dpp_mov<CTRL>(lo32(v)), dpp_mov<CTRL>(hi32(v)));
+}
+
+__device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
+
+__device__ __forceinline__ int64_t wave_min_i64(int64_t v)
+{
+    v = min64(v, dpp_mov64<0xB1>(v));
+    v = min64(v, dpp_mov64<0x4E>(v));
+    v = min64(v, dpp_mov64<0x141>(v));
+    v = min64(v, dpp_mov64<0x140>(v));
+    v = min64(v, i64_from(swz_xor16(lo32(v)), swz_xor16(hi32(v))));
+    v = min64(v, i64_from(xor32(lo32(v)), xor32(hi32(v))));
+    return v;
+}
+
+// inclusive prefix minimum over the 64 lanes (lane l gets min of lanes 0..l)
+__device__ __forceinline__ int64_t wave_prefix_min_i64(int64_t v, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int lo = __shfl_up(lo32(v), off, 64);
+        const int hi = __shfl_up(hi32(v), off, 64);
+        const int64_t o = i64_from(lo, hi);
+        if (lane >= off) v = min64(v, o);
+    }
+    return v;
+}
+
+// ---- host-side launchers (callers validate sizes first; none of these synchronises)
+
+struct PrepBuffers {
+    int32_t *keys[2];        // [cap] each
+    uint32_t *hist;          // [256 * 256]
+    uint32_t *block_cnt;     // [cap / 4096 + 2]
+    int cap;
+};
+
+hipError_t launch_gather_table_values(hipStream_t st, const int32_t *table, int K, int S,
+                                      int32_t inf_key, int32_t *out_keys);
+hipError_t launch_sort_dedup(hipStream_t st, PrepBuffers &pb, int n, int key_bits,
+                             int32_t drop_key, int32_t *out_unique, uint32_t *out_n_unique);
+hipError_t launch_pick_candidates(hipStream_t st, const int32_t *distinct,
+                                  const uint32_t *n_distinct, int n_quantiles, int32_t *cand,
+                                  SolveState *state, int cap);
+hipError_t launch_set_candidates(hipStream_t st, const uint32_t *n_unique, SolveState *state);
+hipError_t launch_rank_lookup(hipStream_t st, const int32_t *tmax, int n, const int32_t *unique,
+                              const uint32_t *n_unique, int32_t *rank_of_orig);
+
+hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
+                              int32_t *t_fast, int32_t *blk_mm);
+
+hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int32_t *table,
+                                     const int32_t *sizes, const int32_t *cand,
+                                     const int32_t *n_cand_p, int32_t *ticket, int64_t *chunk_min,
+                                     int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
+                                     int n_layers, int grid);
+hipError_t launch_recurrence_fast(hipStream_t st, const Problem &p, const int32_t *t_fast,
+                                  const int32_t *blk_mm, const int32_t *sizes, const int32_t *cand,
+                                  SolveState *state, int64_t *chunk_min, int prune, int count_work,
+                                  int descending, int32_t *Fmin, int32_t *Sbest, int grid);
+int fast_kernel_blocks_per_cu(int K);
+
+hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand,
+                           const int32_t *Fmin, const int32_t *Sbest, SolveState *state, int prune,
+                           int64_t *T);
+hipError_t launch_scatter_T(hipStream_t st, const int64_t *T, const int32_t *rank_of_orig,
+                            int n_orig, const SolveState *state, int64_t *out_T);
+hipError_t launch_plan(hipStream_t st, const Problem &p, const int32_t *table, const int32_t *sizes,
+                       SolveState *state, int32_t *F_all, int32_t *tmpFS, void *plan_tmp,
+                       void *best_plan, void *plan_out);
+hipError_t launch_init_state(hipStream_t st, SolveState *state, int64_t *chunk_min, int n_chunks);
+hipError_t launch_init_best_plan(hipStream_t st, void *best_plan);
+
+}  // namespace alpa

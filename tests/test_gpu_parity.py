@@ -1,0 +1,280 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, bit-exact."""
+import hashlib
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2201_12023_amd import binding as B
+from paper_2201_12023_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+INF64 = oracle.INF64
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+KERNELS = {"fast": 0, "generic": B.ALPA_DP_GENERIC}
+
+
+def _same_plan(gpu: dict, ref: oracle.Plan):
+    assert gpu["T_star"] == ref.T_star
+    assert gpu["t_max"] == ref.t_max
+    assert gpu["num_stages"] == ref.num_stages
+    assert gpu["n_evaluated"] == ref.n_evaluated
+    assert gpu["first_layer"] == ref.first_layer
+    assert gpu["shape_idx"] == ref.shape_idx
+
+
+def _full_check(w, kernel_flag, prune):
+    """Every candidate's T*, the candidate list itself, and the plan, against the oracle."""
+    cand_ref = oracle.all_candidates(w.table, w.shapes)
+    T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        assert B.alpa_dp_count_candidates(h) == len(cand_ref)
+        flags = kernel_flag | (B.ALPA_DP_PRUNE if prune else 0)
+        T, plan = B.alpa_dp_solve(h, None, 0, flags)
+        cand = B.alpa_dp_candidates(h)
+        assert (cand == cand_ref).all()
+        assert (T == T_ref).all()
+        _same_plan(plan, p_ref)
+        _same_plan(B.alpa_dp_best(h), p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("kernel", list(KERNELS))
+@pytest.mark.parametrize("prune", [False, True])
+@pytest.mark.parametrize("idx", [1, 2])
+def test_small_workloads_all_candidates(idx, prune, kernel):
+    _full_check(W.make_workload(idx), KERNELS[kernel], prune)
+
+
+RANDOM_CASES = [
+    # seed, K, N, M
+    (0, 1, 1, 1), (1, 2, 1, 2), (2, 3, 2, 2), (3, 5, 1, 4), (4, 6, 2, 4), (5, 7, 3, 2),
+    (6, 9, 3, 4), (7, 12, 2, 8), (8, 17, 4, 4), (9, 16, 1, 8), (10, 33, 2, 2), (11, 20, 5, 4),
+    (12, 10, 8, 8), (13, 40, 3, 8), (14, 64, 1, 2), (15, 13, 7, 8),
+]
+
+
+@pytest.mark.parametrize("kernel", list(KERNELS))
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_random_tables(case, kernel):
+    """Unstructured tables (not monotone in stage length), many infinities and ties; sizes
+    span one to four 16-layer blocks, ragged tails, non-power-of-two device counts."""
+    seed, K, N, M = case
+    rng = np.random.default_rng(seed)
+    w = W.random_problem(seed, K, N, M, inf_frac=float(rng.choice([0.0, 0.2, 0.6])),
+                         value_hi=int(rng.choice([4, 50, 5000])))
+    cand_ref = oracle.all_candidates(w.table, w.shapes)
+    if len(cand_ref) > 300:            # keep the oracle's share of the test short
+        cand_ref = oracle.quantiles(cand_ref, 300)
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            flags = KERNELS[kernel] | (B.ALPA_DP_PRUNE if prune else 0)
+            # an empty list is an argument error at the boundary; an all-infinite table is
+            # reached through the "candidates from the table" mode instead
+            T, plan = B.alpa_dp_solve(h, cand_ref if len(cand_ref) else None, flags=flags)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
+
+
+def test_caller_order_duplicates_and_out_of_table_values():
+    w = W.make_workload(2)
+    allc = oracle.all_candidates(w.table, w.shapes)
+    rng = np.random.default_rng(5)
+    mine = np.concatenate([rng.choice(allc, 200), rng.choice(allc, 50), [0, 1, 2**31 - 2, 7, 7],
+                           allc[-3:]]).astype(np.int32)
+    rng.shuffle(mine)
+    uniq = oracle.sort_dedup(mine)
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, uniq, prune)
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            T, plan = B.alpa_dp_solve(h, mine, flags=B.ALPA_DP_PRUNE if prune else 0)
+            assert (B.alpa_dp_candidates(h) == uniq).all()
+            pos = np.searchsorted(uniq, mine)
+            assert (T == T_ref[pos]).all()
+            _same_plan(plan, p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
+
+
+def test_quantile_mode_and_errors():
+    w = W.make_workload(2)
+    allc = oracle.all_candidates(w.table, w.shapes)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        for Q in (2, 3, 64, 257, len(allc), len(allc) + 5):
+            cand = oracle.quantiles(allc, Q)
+            T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, cand, False)
+            T, plan = B.alpa_dp_solve(h, None, Q, 0)
+            assert (B.alpa_dp_candidates(h) == cand).all()
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+        L = B.load()
+        assert L.alpa_dp_solve(h, None, 1, 0, None, None) == -1
+        assert L.alpa_dp_solve(h, None, -1, 0, None, None) == -1
+        bad = np.asarray([5, -1], np.int32)
+        assert L.alpa_dp_solve(h, bad.ctypes.data, 2, 0, None, None) == -1
+        bad = np.asarray([5, 2**31 - 1], np.int32)
+        assert L.alpa_dp_solve(h, bad.ctypes.data, 2, 0, None, None) == -1
+        assert L.alpa_dp_solve(h, bad.ctypes.data, 0, 0, None, None) == -1
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+def test_infeasible_and_degenerate_problems():
+    # every entry infinite
+    w = W.random_problem(1, 4, 2, 2, inf_frac=1.0)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        assert B.alpa_dp_count_candidates(h) == 0
+        T, plan = B.alpa_dp_solve(h, None, 0, 0)
+        assert len(T) == 0 and plan["T_star"] == INF64 and plan["num_stages"] == 0
+        T, plan = B.alpa_dp_solve(h, [3, 9], flags=B.ALPA_DP_PRUNE)
+        assert (T == INF64).all() and plan["T_star"] == INF64 and plan["n_evaluated"] == 2
+    finally:
+        B.alpa_dp_destroy(h)
+    # more devices than layers with one-device submeshes only: no plan
+    shapes = np.asarray([[1, 1]], np.int32)
+    table = np.full((3, 3, 3, 1), 5, np.int32)
+    h = B.alpa_dp_create(table, 3, 4, 1, 2, shapes)
+    try:
+        T, plan = B.alpa_dp_solve(h, None, 0, 0)
+        assert (T == INF64).all() and plan["num_stages"] == 0
+    finally:
+        B.alpa_dp_destroy(h)
+    # a candidate below every entry
+    w = W.make_workload(1)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        T, plan = B.alpa_dp_solve(h, [0, 1])
+        assert (T == INF64).all() and plan["T_star"] == INF64
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+def test_prune_breaks_on_equality_gpu():
+    K, Bm = 2, 2
+    shapes = np.asarray([[1, 1], [2, 1]], np.int32)
+    table = np.full((K, K, K, 2), 2**31 - 1, np.int64)
+    table[:, 0, 0, 0] = 2
+    table[:, 1, 1, 0] = 2
+    table[:, 0, 1, 1] = 3
+    table = table.astype(np.int32)
+    for kf in KERNELS.values():
+        h = B.alpa_dp_create(table, K, 2, 1, Bm, shapes)
+        try:
+            T, plan = B.alpa_dp_solve(h, None, 0, kf | B.ALPA_DP_PRUNE)
+            assert list(T) == [6, INF64] and plan["n_evaluated"] == 1 and plan["t_max"] == 2
+            T, plan = B.alpa_dp_solve(h, None, 0, kf)
+            assert list(T) == [6, 6] and plan["n_evaluated"] == 2 and plan["t_max"] == 2
+        finally:
+            B.alpa_dp_destroy(h)
+
+
+def test_best_over_several_solves_and_set_B():
+    w = W.make_workload(2)
+    allc = oracle.all_candidates(w.table, w.shapes)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        lo, hi = allc[: len(allc) // 3], allc[len(allc) // 3:]
+        _, p_hi = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, hi, False)
+        _, p_lo = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, lo, False)
+        _, g_hi = B.alpa_dp_solve(h, hi)
+        _same_plan(g_hi, p_hi)
+        _, g_lo = B.alpa_dp_solve(h, lo)
+        _same_plan(g_lo, p_lo)
+        best = B.alpa_dp_best(h)
+        ref = min([p_hi, p_lo], key=lambda p: (p.T_star, p.t_max))
+        _same_plan(best, ref)
+        # another B: Eq. 4 and the pruning rule change, F does not
+        B.alpa_dp_set_B(h, 3)
+        T_ref, p_ref = oracle.solve(w.table, w.N, w.M, 3, w.shapes, allc, True)
+        T, plan = B.alpa_dp_solve(h, None, 0, B.ALPA_DP_PRUNE)
+        assert (T == T_ref).all()
+        _same_plan(plan, p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
+    # alpa_dp_best on a fresh handle runs the full pruned loop itself
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        _, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, allc, True)
+        _same_plan(B.alpa_dp_best(h), p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+def test_device_pointer_variant_on_a_torch_stream():
+    import torch
+    w = W.make_workload(2)
+    allc = oracle.all_candidates(w.table, w.shapes)
+    cand = oracle.quantiles(allc, 500)
+    T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, cand, False)
+    st = torch.cuda.Stream()
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        B.alpa_dp_set_stream(h, st)
+        with torch.cuda.stream(st):
+            d_t = torch.from_numpy(cand[::-1].copy()).to("cuda", non_blocking=False)
+            d_T = torch.empty(len(cand), dtype=torch.int64, device="cuda")
+            d_plan = torch.zeros(B.PLAN_BYTES, dtype=torch.uint8, device="cuda")
+        st.synchronize()
+        for _ in range(3):
+            B.alpa_dp_solve_dev(h, d_t, len(cand), 0, d_T, d_plan)
+        st.synchronize()
+        assert (d_T.cpu().numpy()[::-1] == T_ref).all()
+        _same_plan(B.plan_from_bytes(d_plan.cpu().numpy().tobytes()), p_ref)
+        tm = B.alpa_dp_last_timing(h)
+        assert tm["ms_recurrence"] > 0
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("idx", [3, 4, 5])
+def test_full_size_workloads_against_stored_oracle_results(idx):
+    """Workloads 3-5 at full size in the launch configuration the benchmark times.  The
+    expected values were written by tests/golden/make_golden.py from the oracle alone."""
+    g = json.load(open(os.path.join(GOLD, f"workload_{idx}.json")))
+    w = W.make_workload(idx)
+    assert hashlib.sha256(w.table.tobytes()).hexdigest() == g["table_sha256"]
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        assert B.alpa_dp_count_candidates(h) == g["n_distinct"]
+        nq = w.n_quantiles if w.candidates == "quantiles" else 0
+        T, plan = B.alpa_dp_solve(h, None, nq, B.ALPA_DP_PRUNE if w.prune else 0)
+        cand = B.alpa_dp_candidates(h)
+        assert len(cand) == g["n_candidates"]
+        assert hashlib.sha256(cand.astype("<i4").tobytes()).hexdigest() == g["cand_sha256"]
+        assert [int(x) for x in T[::97]] == g["T_every_97"]
+        assert hashlib.sha256(T.astype("<i8").tobytes()).hexdigest() == g["T_sha256"]
+        for key in ("T_star", "t_max", "num_stages", "n_evaluated", "first_layer", "shape_idx"):
+            assert plan[key] == g["plan"][key], key
+        # a few candidates recomputed by the oracle now, one by one
+        pick = np.linspace(0, len(cand) - 1, 6).astype(int)
+        T_o, _ = oracle.eval_candidates(w.table, w.N, w.M, w.B, w.shapes, cand[pick], threads=6)
+        assert (T[pick] == T_o).all()
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+def test_general_kernel_on_a_mesh_larger_than_64_devices():
+    """N*M = 80 and K = 66 are outside the register/LDS kernel; the general one serves."""
+    w = W.random_problem(77, 66, 10, 8, inf_frac=0.3, value_hi=900)
+    allc = oracle.all_candidates(w.table, w.shapes)
+    cand = oracle.quantiles(allc, 8)
+    T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand, False, 8)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        T, plan = B.alpa_dp_solve(h, cand)
+        assert (T == T_ref).all()
+        _same_plan(plan, p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
