@@ -83,8 +83,8 @@ static int alloc_candidate_arrays(alpa_dp *h, int cap)
     HIPCHK(hipMalloc(&h->d_cand, c * 4));
     HIPCHK(hipMalloc(&h->d_rank, c * 4));
     HIPCHK(hipMalloc(&h->d_tmax_stage, c * 4));
-    HIPCHK(hipMalloc(&h->d_Fmin, c * 4));
-    HIPCHK(hipMalloc(&h->d_Sbest, c * 4));
+    HIPCHK(hipMalloc(&h->d_Fmin, (c + 1) * 4));      // + one spare slot (see FastArgs)
+    HIPCHK(hipMalloc(&h->d_Sbest, (c + 1) * 4));
     HIPCHK(hipMalloc(&h->d_T, c * 8));
     HIPCHK(hipMalloc(&h->d_outT_stage, c * 8));
     HIPCHK(hipMalloc(&h->d_chunkmin, (c / PRUNE_CHUNK + 2) * 8));
@@ -189,7 +189,7 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
         HIPCHK(hipMalloc(&h->d_ncount, 2 * 4));
         HIPCHK(hipMalloc(&h->d_state, sizeof(SolveState)));
         HIPCHK(hipMemsetAsync(h->d_state, 0, sizeof(SolveState), h->stream));
-        HIPCHK(hipMalloc(&h->d_tmpFS, 2 * 4));
+        HIPCHK(hipMalloc(&h->d_tmpFS, 4 * 4));
         HIPCHK(hipMalloc(&h->d_plan_tmp, sizeof(alpa_plan_t)));
         HIPCHK(hipMalloc(&h->d_best_plan, sizeof(alpa_plan_t)));
         HIPCHK(launch_init_best_plan(h->stream, h->d_best_plan));
@@ -307,10 +307,11 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         const bool fast = h->fast_ok && !(flags & ALPA_DP_GENERIC);
         if (fast) {
             const int grid = std::max(1, std::min(bound, h->fast_grid_max));
-            HIPCHK(launch_recurrence_fast(st, p, h->d_tfast, h->d_blkmm, h->d_sizes, h->d_cand,
-                                          h->d_state, h->d_chunkmin, prune,
-                                          /*count_work=*/(flags & ALPA_DP_COUNT_WORK) ? 1 : 0,
-                                          /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest,
+            FastArgs fa{p, h->d_tfast, h->d_blkmm, h->d_sizes, h->d_cand, &h->d_state->n_cand,
+                        &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
+                        /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr};
+            HIPCHK(launch_recurrence_fast(st, fa, (flags & ALPA_DP_COUNT_WORK) ? FAST_MODE_COUNT
+                                                                              : FAST_MODE_BATCH,
                                           grid));
         } else {
             const int grid = std::max(1, std::min(bound, h->generic_grid_max));
@@ -325,8 +326,19 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (d_out_T && bound > 0)
         HIPCHK(launch_scatter_T(st, h->d_T, have_list ? h->d_rank : nullptr,
                                 have_list ? n_tmax : bound, h->d_state, d_out_T));
-    HIPCHK(launch_plan(st, p, h->d_table, h->d_sizes, h->d_state, h->d_Fall, h->d_tmpFS,
-                       h->d_plan_tmp, h->d_best_plan, d_out_plan));
+    // every layer of the winning candidate (does nothing if there is none), then the walk
+    if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
+        FastArgs fa{p, h->d_tfast, h->d_blkmm, h->d_sizes, &h->d_state->best_c,
+                    &h->d_state->plan_n, &h->d_state->plan_ticket, &h->d_state->wave_relax,
+                    nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall};
+        HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1));
+    } else {
+        HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, &h->d_state->best_c,
+                                         &h->d_state->plan_n, &h->d_state->plan_ticket, nullptr, 0,
+                                         h->d_tmpFS, h->d_tmpFS + 2, h->d_Fall, p.Smax + 1, 1));
+    }
+    HIPCHK(launch_plan_walk(st, p, h->d_table, h->d_sizes, h->d_state, h->d_Fall, h->d_plan_tmp,
+                            h->d_best_plan, d_out_plan));
     HIPCHK(hipEventRecord(h->ev[3], st));
     h->any_solve = true;
     h->timed = true;

@@ -134,10 +134,19 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      const int32_t *n_cand_p, int32_t *ticket, int64_t *chunk_min,
                                      int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
                                      int n_layers, int grid);
-hipError_t launch_recurrence_fast(hipStream_t st, const Problem &p, const int32_t *t_fast,
-                                  const int32_t *blk_mm, const int32_t *sizes, const int32_t *cand,
-                                  SolveState *state, int64_t *chunk_min, int prune, int count_work,
-                                  int descending, int32_t *Fmin, int32_t *Sbest, int grid);
+struct FastArgs {
+    Problem p;
+    const int32_t *t_fast, *blk_mm, *sizes, *cand, *n_cand_p;
+    int32_t *ticket;
+    unsigned long long *wave_relax;
+    int64_t *chunk_min;
+    int prune, descending;
+    int32_t *Fmin, *Sbest;
+    int dummy_idx;           // spare slot of Fmin / Sbest for the waves that own no result
+    int32_t *F_all;          // [Smax+1][(K+2)*(D+1)], plan mode only
+};
+enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
+hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int grid);
 int fast_kernel_blocks_per_cu(int K);
 
 hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand,
@@ -145,9 +154,9 @@ hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand
                            int64_t *T);
 hipError_t launch_scatter_T(hipStream_t st, const int64_t *T, const int32_t *rank_of_orig,
                             int n_orig, const SolveState *state, int64_t *out_T);
-hipError_t launch_plan(hipStream_t st, const Problem &p, const int32_t *table, const int32_t *sizes,
-                       SolveState *state, int32_t *F_all, int32_t *tmpFS, void *plan_tmp,
-                       void *best_plan, void *plan_out);
+hipError_t launch_plan_walk(hipStream_t st, const Problem &p, const int32_t *table,
+                            const int32_t *sizes, SolveState *state, const int32_t *F_all,
+                            void *plan_tmp, void *best_plan, void *plan_out);
 hipError_t launch_init_state(hipStream_t st, SolveState *state, int64_t *chunk_min, int n_chunks);
 hipError_t launch_init_best_plan(hipStream_t st, void *best_plan);
 

@@ -355,14 +355,10 @@ hipError_t launch_scatter_T(hipStream_t st, const int64_t *T, const int32_t *ran
     return hipGetLastError();
 }
 
-hipError_t launch_plan(hipStream_t st, const Problem &p, const int32_t *table, const int32_t *sizes,
-                       SolveState *state, int32_t *F_all, int32_t *tmpFS, void *plan_tmp,
-                       void *best_plan, void *plan_out)
+hipError_t launch_plan_walk(hipStream_t st, const Problem &p, const int32_t *table,
+                            const int32_t *sizes, SolveState *state, const int32_t *F_all,
+                            void *plan_tmp, void *best_plan, void *plan_out)
 {
-    // every layer of the winning candidate (one workgroup; does nothing if infeasible)
-    hipLaunchKernelGGL(recurrence_generic_kernel, dim3(1), dim3(256), 0, st, p, table, sizes,
-                       &state->best_c, &state->plan_n, &state->plan_ticket, (int64_t *)nullptr, 0,
-                       tmpFS, tmpFS + 1, F_all, p.Smax + 1);
     hipLaunchKernelGGL(plan_walk_kernel, dim3(1), dim3(WAVE), 0, st, p, table, sizes, state, F_all,
                        (PlanDev *)plan_tmp, (PlanDev *)best_plan);
     if (plan_out && plan_out != plan_tmp)
