@@ -43,7 +43,7 @@ struct alpa_dp {
     int KP = 0;
     int fast_grid_max = 0, generic_grid_max = 0;
 
-    int32_t *d_table = nullptr, *d_sizes = nullptr, *d_tfast = nullptr, *d_blkmm = nullptr;
+    int32_t *d_table = nullptr, *d_sizes = nullptr, *d_recs = nullptr;
     PrepBuffers pb{};
     int32_t *d_distinct = nullptr;
     uint32_t *d_ncount = nullptr;   // [2]: distinct table values, distinct caller candidates
@@ -121,7 +121,7 @@ extern "C" void alpa_dp_destroy(alpa_dp_t *h)
     (void)hipSetDevice(h->device);
     (void)hipStreamSynchronize(h->stream);
     free_candidate_arrays(h);
-    (void)hipFree(h->d_table); (void)hipFree(h->d_sizes); (void)hipFree(h->d_tfast); (void)hipFree(h->d_blkmm);
+    (void)hipFree(h->d_table); (void)hipFree(h->d_sizes); (void)hipFree(h->d_recs);
     (void)hipFree(h->pb.hist); (void)hipFree(h->d_ncount); (void)hipFree(h->d_state); (void)hipFree(h->d_scratch);
     (void)hipFree(h->d_Fall); (void)hipFree(h->d_tmpFS); (void)hipFree(h->d_plan_tmp); (void)hipFree(h->d_best_plan);
     for (auto &e : h->ev) if (e) (void)hipEventDestroy(e);
@@ -204,9 +204,9 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
         h->fast_ok = K <= 64 && D <= 64;
         if (h->fast_ok) {
             h->KP = 16 * ((K + 15) / 16);
-            HIPCHK(hipMalloc(&h->d_tfast, (size_t)K * K * S * h->KP * 4));
-            HIPCHK(hipMalloc(&h->d_blkmm, (size_t)K * K * S * 8 * 4));
-            HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_tfast, h->d_blkmm));
+            HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
+            HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
+            HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
             const int per_cu = fast_kernel_blocks_per_cu(K);
             if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
             h->fast_grid_max = h->n_cu * per_cu;
@@ -307,7 +307,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         const bool fast = h->fast_ok && !(flags & ALPA_DP_GENERIC);
         if (fast) {
             const int grid = std::max(1, std::min(bound, h->fast_grid_max));
-            FastArgs fa{p, h->d_tfast, h->d_blkmm, h->d_sizes, h->d_cand, &h->d_state->n_cand,
+            FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
                         /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr};
             HIPCHK(launch_recurrence_fast(st, fa, (flags & ALPA_DP_COUNT_WORK) ? FAST_MODE_COUNT
@@ -328,7 +328,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
                                 have_list ? n_tmax : bound, h->d_state, d_out_T));
     // every layer of the winning candidate (does nothing if there is none), then the walk
     if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
-        FastArgs fa{p, h->d_tfast, h->d_blkmm, h->d_sizes, &h->d_state->best_c,
+        FastArgs fa{p, h->d_recs, h->d_sizes, &h->d_state->best_c,
                     &h->d_state->plan_n, &h->d_state->plan_ticket, &h->d_state->wave_relax,
                     nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall};
         HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1));

@@ -127,7 +127,8 @@ hipError_t launch_rank_lookup(hipStream_t st, const int32_t *tmax, int n, const 
                               const uint32_t *n_unique, int32_t *rank_of_orig);
 
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
-                              int32_t *t_fast, int32_t *blk_mm);
+                              int32_t *recs);
+size_t fast_table_ints(int K, int S);    // size of the column-record array, padding included
 
 hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int32_t *table,
                                      const int32_t *sizes, const int32_t *cand,
@@ -136,7 +137,7 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      int n_layers, int grid);
 struct FastArgs {
     Problem p;
-    const int32_t *t_fast, *blk_mm, *sizes, *cand, *n_cand_p;
+    const int32_t *recs, *sizes, *cand, *n_cand_p;
     int32_t *ticket;
     unsigned long long *wave_relax;
     int64_t *chunk_min;

@@ -2,25 +2,29 @@
 //
 // Mapping.  One workgroup evaluates one t_max candidate at a time (persistent workgroups
 // draw candidates from a ticket counter).  Lane l of every wave owns device count
-// d = l + 1.  The first layers k are cut into blocks of 16; wave (wk, wi) of the
-// workgroup owns block wk and keeps its 16 accumulators F(s, k, .) in VGPRs; with WI > 1
-// the (last layer) columns are dealt round-robin over the wi and the partial minima are
-// merged through LDS.  The previous layer F(s-1, ., .) lives in LDS, one row of 64 lanes
-// per first layer.  For a fixed (last layer i, shape q) the operand F(s-1, i+1, d - a_q)
-// is one lane-shifted LDS row read, reused for the 16 first layers of the block, and
-// t_intra(k..i, q, s) is the same for all lanes: it is fetched with scalar loads and used
-// as the scalar operand of the add, so a cell-update costs one v_add and one v_min.  The
-// filter t_intra <= t_max is wave-uniform; it is resolved per block from the block's
-// precomputed min / max (skip, take unfiltered, or select per entry).  Infinite entries
-// need no filter: DEV_INF + anything >= DEV_INF and accumulators start at DEV_INF.
-// Lanes with d <= a_q are switched off for the whole column loop of shape q.
+// d = l + 1.  The first layers k are cut into half-blocks of 8; a workgroup has NWK =
+// ceil(K / 16) waves along that axis and wave w owns half-blocks w ("A") and 2*NWK-1-w
+// ("B"): the triangular work (a column with last layer i only touches first layers <= i)
+// is then the same for every wave.  The 16 accumulators F(s, k, .) of a wave live in VGPRs;
+// with WI > 1 the (last layer) columns are dealt round-robin over WI wave groups and the
+// partial minima are merged through LDS.  The previous layer F(s-1, ., .) lives in LDS, one
+// row of 64 lanes per first layer.  For a fixed (last layer i, shape q) the operand
+// F(s-1, i+1, d - a_q) is one lane-shifted LDS row read, reused for all first layers of the
+// wave, and t_intra(k..i, q, s) is the same for all lanes: it is fetched with scalar loads
+// and used as the scalar operand of the add, so a cell-update costs one v_add and one v_min.
+// The filter t_intra <= t_max is wave-uniform; it is resolved per half-block from its
+// precomputed min / max (skip, take unfiltered, or select per entry on the scalar unit).
+// Infinite entries need no filter: DEV_INF + anything >= DEV_INF and accumulators start at
+// DEV_INF.  Column loads (scalars and the LDS row) are issued one column ahead.
 //
-// Table layout (built once per handle by repack_fast_kernel):
-//   t_fast [s-1][q][i][kp]   kp = 0..KP-1 (KP = 16 * ceil(K/16)) = first layer (0-based),
-//                            i = last layer (0-based); DEV_INF where kp > i, kp >= K or
-//                            the entry is +infinity;
-//   blk_mm [s-1][q][i][b][2] b = 0..3: {min over the block's entries, max over its finite
-//                            entries (-1 if none)} for first layers 16b..16b+15.
+// Table layout (built once per handle by repack_fast_kernel): one record of KP + 16 int32
+// per column (s-1, q, i), columns in that order (i fastest), KP = 16 * ceil(K/16):
+//   rec[kp], kp = 0..KP-1    t_intra for first layer kp (0-based) and last layer i; DEV_INF
+//                            where kp > i, kp >= K or the entry is +infinity;
+//   rec[KP + 2 hb + {0,1}]   hb = 0..7: {min, max} over the finite entries of first layers
+//                            8hb..8hb+7 ({DEV_INF, DEV_INF} if there is none).
+// The array is padded by a few records so that the one-column-ahead loads may run past the
+// last column.
 #include "internal.hpp"
 
 namespace alpa {
@@ -28,55 +32,82 @@ namespace alpa {
 typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-load path
 
 __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int S, int KP,
-                                   int32_t *__restrict__ t_fast, int32_t *__restrict__ blk_mm)
+                                   int32_t *__restrict__ recs)
 {
-    // one thread per (s, q, i, b): fills 16 entries and their summary
-    const long long total = (long long)K * S * K * 4;
+    // one thread per (s, q, i, hb): fills 8 entries and their summary
+    const int REC = KP + 16;
+    const long long total = (long long)K * S * K * 8;
     for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
          e += (long long)gridDim.x * blockDim.x) {
-        const int b = (int)(e & 3);
-        long long r = e >> 2;
+        const int hb = (int)(e & 7);
+        long long r = e >> 3;
         const int i = (int)(r % K); r /= K;
         const int q = (int)(r % S);
         const int s = (int)(r / S);
-        const long long col = ((long long)s * S + q) * K + i;
+        int32_t *rec = recs + (((long long)s * S + q) * K + i) * REC;
         int32_t mn = DEV_INF, mx = -1;
-        if (16 * b < KP) {
-            int32_t *dst = t_fast + col * KP + 16 * b;
-            for (int u = 0; u < 16; ++u) {
-                const int k = 16 * b + u;
+        if (8 * hb < KP) {
+            for (int u = 0; u < 8; ++u) {
+                const int k = 8 * hb + u;
                 int32_t v = DEV_INF;
                 if (k <= i && k < K) {
                     const int32_t t = table[(((long long)s * K + k) * K + i) * S + q];
                     if (t != INF_I32) v = t;
                 }
-                dst[u] = v;
+                rec[k] = v;
                 if (v < DEV_INF) { mn = min(mn, v); mx = max(mx, v); }
             }
         }
-        int32_t *mm = blk_mm + (col * 4 + b) * 2;
-        mm[0] = mn;
-        mm[1] = mx;
+        rec[KP + 2 * hb + 0] = mn;
+        rec[KP + 2 * hb + 1] = (mx < 0) ? DEV_INF : mx;
     }
 }
 
-// One (last layer, shape) column against the 16 first layers of this wave's block.
-template <bool COUNT>
-__device__ __forceinline__ void column(int32_t (&acc)[16], cptr_t tp, cptr_t mm, int32_t G,
-                                       int32_t c, unsigned &n_blocks)
+// One half-block's share of a column, loaded one step ahead of its use.
+struct HalfColumn {
+    int32_t t[8];              // t_intra for 8 first layers (scalar registers)
+    int32_t mn, mx;            // the half-block's min / max over finite entries
+};
+
+__device__ __forceinline__ void load_half(HalfColumn &h, cptr_t tp, cptr_t mm)
 {
-    const int32_t mn = mm[0], mx = mm[1];
-    if (mn > c) return;                       // nothing in the block passes the filter
-    if (COUNT) ++n_blocks;
-    int32_t t[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) t[u] = tp[u];
-    if (mx > c) {                             // mixed block: filter entry by entry (scalar)
+    for (int u = 0; u < 8; ++u) h.t[u] = tp[u];
+    h.mn = mm[0];
+    h.mx = mm[1];
+}
+
+// Makes loaded values "used" here, so that the wait for them is placed before the next
+// loads are issued (scalar loads return out of order: any later wait would also wait for
+// the loads just issued).  The memory clobber keeps later loads below this point.
+__device__ __forceinline__ void settle(const HalfColumn &h)
+{
+    asm volatile("" :: "s"(h.t[0]), "s"(h.t[1]), "s"(h.t[2]), "s"(h.t[3]), "s"(h.t[4]),
+                       "s"(h.t[5]), "s"(h.t[6]), "s"(h.t[7]), "s"(h.mn), "s"(h.mx)
+                 : "memory");
+}
+__device__ __forceinline__ void settle(const HalfColumn &h, int32_t f)
+{
+    asm volatile("" :: "s"(h.t[0]), "s"(h.t[1]), "s"(h.t[2]), "s"(h.t[3]), "s"(h.t[4]),
+                       "s"(h.t[5]), "s"(h.t[6]), "s"(h.t[7]), "s"(h.mn), "s"(h.mx), "v"(f)
+                 : "memory");
+}
+__device__ __forceinline__ void fence_loads() { asm volatile("" ::: "memory"); }
+
+// Eight first layers against one column: unfiltered when every finite entry passes, skipped
+// when none does, else filtered entry by entry on the scalar unit.
+template <bool COUNT>
+__device__ __forceinline__ void relax8(int32_t *acc, int32_t (&t)[8], int32_t mn, int32_t mx,
+                                       int32_t G, int32_t c, unsigned &n_blocks)
+{
+    if (mx > c) {
+        if (mn > c) return;                   // nothing in the half-block passes the filter
 #pragma unroll
-        for (int u = 0; u < 16; ++u) t[u] = (t[u] <= c) ? t[u] : DEV_INF;
+        for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c) ? t[u] : DEV_INF;
     }
+    if (COUNT) ++n_blocks;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) acc[u] = min(acc[u], t[u] + G);
+    for (int u = 0; u < 8; ++u) acc[u] = min(acc[u], t[u] + G);
 }
 
 // Lower-index evidence for the pruning rule (see recurrence_generic_kernel).
@@ -97,28 +128,31 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // own the result.
 template <int NWK, int WI, bool DUMP, bool COUNT>
 __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
-    Problem p, const int32_t *__restrict__ t_fast_g, const int32_t *__restrict__ blk_mm_g,
-    const int32_t *__restrict__ sizes_g, const int32_t *__restrict__ cand,
+    Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g, const int32_t *__restrict__ cand,
     const int32_t *__restrict__ n_cand_p, int32_t *ticket, unsigned long long *wave_relax,
     int64_t *chunk_min, int prune, int descending, int32_t *__restrict__ Fmin,
     int32_t *__restrict__ Sbest, int dummy_idx, int32_t *__restrict__ F_all)
 {
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
-    extern __shared__ int32_t lds[];                   // Fprev [KP][64] (+ Fnext [KP][64])
+    extern __shared__ int32_t lds[];                   // Fprev [KP+WI][64] (+ Fnext, same size)
     __shared__ int32_t sh_tk[NT];
     __shared__ int32_t sh_skip[NWK * WI];
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wid % NWK, wi = wid / NWK;
+    const int hbA = wk, hbB = 2 * NWK - 1 - wk;        // the wave's two half-blocks of 8 first layers
+    const int rowA = 8 * hbA, rowB = 8 * hbB;
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
-    const cptr_t t_fast = (cptr_t)t_fast_g;
-    const cptr_t blk_mm = (cptr_t)blk_mm_g;
+    constexpr int REC = KP + 16;                       // int32 per column record
+    const cptr_t recs = (cptr_t)recs_g;
+    const int oA = rowA, oB = rowB;                    // record offsets of the wave's operands
+    const int omA = KP + 2 * hbA, omB = KP + 2 * hbB;
     const cptr_t sizes = (cptr_t)sizes_g;
     int32_t *Fprev = lds;
-    int32_t *Fnext = lds + KP * WAVE;
+    int32_t *Fnext = lds + (KP + WI) * WAVE;
     const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
     unsigned long long n_blocks_total = 0;
 
@@ -154,47 +188,103 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
         int32_t best = DEV_INF, sbest = 0;
         unsigned n_blocks = 0;
         for (int s = 1; s <= p.Smax; ++s) {
-            int32_t acc[16];
+            int32_t acc[16];                           // [0..7] half-block A, [8..15] half-block B
 #pragma unroll
             for (int u = 0; u < 16; ++u) acc[u] = DEV_INF;
             const int i_lo = (s == 1) ? K - 1 : 0;     // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
-            const int i0 = max(i_lo, 16 * wk) + wi;    // columns with a first layer in this block
+            const int i0 = max(i_lo, rowA) + wi;       // columns that reach half-block A
             if (WI > 1) {
-                for (int x = tid; x < KP * WAVE; x += NT) Fnext[x] = DEV_INF;
+                for (int x = tid; x < (KP + WI) * WAVE; x += NT) Fnext[x] = DEV_INF;
             }
             for (int q = 0; q < S; ++q) {
                 const int a = sizes[q];
                 if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
-                const size_t colq = ((size_t)(s - 1) * S + q) * K;
+                if (i0 > i_hi) continue;
+                cptr_t rec = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
+                const cptr_t rec_last = rec + (size_t)(i_hi - i0) * REC;
+                HalfColumn hA, hB;
                 if (s == 1) {
-                    const int32_t G = (lane + 1 == a) ? 0 : DEV_INF;     // F(0, K+1, 0) = 0
-                    for (int i = i0; i <= i_hi; i += WI)
-                        column<COUNT>(acc, t_fast + (colq + i) * KP + 16 * wk,
-                                      blk_mm + ((colq + i) * 4 + wk) * 2, G, c, n_blocks);
-                } else {
-                    const bool live = lane >= a;       // d - a_q >= 1
-                    const int32_t *row = Fprev + (live ? lane - a : 0);
-                    for (int i = i0; i <= i_hi; i += WI) {
-                        const int32_t f = row[(i + 1) * WAVE];           // F(s-1, i+1, d-a)
-                        const int32_t G = live ? f : DEV_INF;
-                        column<COUNT>(acc, t_fast + (colq + i) * KP + 16 * wk,
-                                      blk_mm + ((colq + i) * 4 + wk) * 2, G, c, n_blocks);
+                    // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
+                    const int32_t G = (lane + 1 == a) ? 0 : DEV_INF;
+                    int i = i0;
+                    for (; rec <= rec_last; rec += REC * WI, i += WI) {
+                        load_half(hA, rec + oA, rec + omA);
+                        load_half(hB, rec + oB, rec + omB);
+                        relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                        if (i >= rowB) relax8<COUNT>(acc + 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                     }
+                    continue;
+                }
+                // Pipeline, one step ahead: while half-block A of a column is computed the
+                // loads for its half-block B are in flight, and while B is computed the loads
+                // for A of the next column (and that column's LDS row) are.  The loads after
+                // the last column land in the padding and are dropped.
+                const bool live = lane >= a;           // d - a_q >= 1
+                const int32_t *frow = Fprev + (live ? lane - a : 0) + (i0 + 1) * WAVE;   // row i+1
+                int32_t f = *frow;
+                load_half(hA, rec + oA, rec + omA);
+                fence_loads();
+                // columns that only reach half-block A, two per trip (hB serves as the
+                // second buffer); an odd one is done without overlap
+                constexpr int STEP = REC * WI;
+                int n1 = min((rowB - i0 + WI - 1) / WI, (i_hi - i0) / WI + 1);
+                for (; n1 >= 2; n1 -= 2, rec += 2 * STEP) {
+                    settle(hA, f);
+                    frow += WAVE * WI;
+                    int32_t f2 = *frow;
+                    load_half(hB, rec + STEP + oA, rec + STEP + omA);
+                    fence_loads();
+                    const int32_t G = live ? f : DEV_INF;
+                    relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                    settle(hB, f2);
+                    frow += WAVE * WI;
+                    f = *frow;
+                    load_half(hA, rec + 2 * STEP + oA, rec + 2 * STEP + omA);
+                    fence_loads();
+                    const int32_t G2 = live ? f2 : DEV_INF;
+                    relax8<COUNT>(acc, hB.t, hB.mn, hB.mx, G2, c, n_blocks);
+                }
+                if (n1 == 1) {
+                    const int32_t G = live ? f : DEV_INF;
+                    relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                    rec += STEP;
+                    frow += WAVE * WI;
+                    f = *frow;
+                    load_half(hA, rec + oA, rec + omA);
+                    fence_loads();
+                }
+                // columns that reach both half-blocks
+                for (; rec <= rec_last; rec += STEP) {
+                    settle(hA, f);
+                    load_half(hB, rec + oB, rec + omB);
+                    fence_loads();
+                    const int32_t G = live ? f : DEV_INF;
+                    relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                    settle(hB);
+                    frow += WAVE * WI;
+                    f = *frow;
+                    load_half(hA, rec + STEP + oA, rec + STEP + omA);
+                    fence_loads();
+                    relax8<COUNT>(acc + 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                 }
             }
             __syncthreads();                           // every wave is done reading Fprev
             int32_t f1;
             if (WI == 1) {
 #pragma unroll
-                for (int u = 0; u < 16; ++u)           // rows 0 and >= K are never operands
-                    Fprev[(16 * wk + u) * WAVE + lane] = acc[u];
+                for (int u = 0; u < 8; ++u) {          // rows 0 and >= K are never operands
+                    Fprev[(rowA + u) * WAVE + lane] = acc[u];
+                    Fprev[(rowB + u) * WAVE + lane] = acc[8 + u];
+                }
                 __syncthreads();
-                f1 = acc[0];                           // F(s, first layer, .) in the wk = 0 wave
+                f1 = acc[0];                           // F(s, first layer, .) in wave 0 (half-block 0)
             } else {
 #pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    atomicMin(&Fnext[(16 * wk + u) * WAVE + lane], acc[u]);
+                for (int u = 0; u < 8; ++u) {
+                    atomicMin(&Fnext[(rowA + u) * WAVE + lane], acc[u]);
+                    atomicMin(&Fnext[(rowB + u) * WAVE + lane], acc[8 + u]);
+                }
                 __syncthreads();
                 int32_t *tmp = Fprev; Fprev = Fnext; Fnext = tmp;
                 f1 = Fprev[lane];                      // row 0 holds F(s, first layer, .)
@@ -205,7 +295,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 if (WI == 1) {
 #pragma unroll
                     for (int u = 0; u < 16; ++u) {
-                        const int k = 16 * wk + u;
+                        const int k = (u < 8 ? rowA : rowB - 8) + u;
                         const bool in = lane < D;
                         if (k < K) Fs[(k + 1) * (D + 1) + (in ? lane + 1 : 0)] = in ? acc[u] : DEV_INF;
                     }
@@ -236,18 +326,23 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
         if (COUNT) n_blocks_total += n_blocks;
         __syncthreads();                               // LDS is reused by the next candidate
     }
-    if (COUNT) atomicAdd(wave_relax, lane == 0 ? n_blocks_total * 16ull : 0ull);
+    if (COUNT) atomicAdd(wave_relax, lane == 0 ? n_blocks_total * 8ull : 0ull);
 }
 
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
-                              int32_t *t_fast, int32_t *blk_mm)
+                              int32_t *recs)
 {
-    long long total = (long long)K * K * S * 4;
+    long long total = (long long)K * K * S * 8;
     int grid = (int)((total + 255) / 256);
     if (grid > 8192) grid = 8192;
-    hipLaunchKernelGGL(repack_fast_kernel, dim3(grid), dim3(256), 0, st, table, K, S, KP, t_fast,
-                       blk_mm);
+    hipLaunchKernelGGL(repack_fast_kernel, dim3(grid), dim3(256), 0, st, table, K, S, KP, recs);
     return hipGetLastError();
+}
+
+size_t fast_table_ints(int K, int S)
+{
+    const int KP = 16 * ((K + 15) / 16);
+    return ((size_t)K * S * K + 8) * (size_t)(KP + 16);     // 8 records of padding
 }
 
 constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (plan) run
@@ -255,9 +350,9 @@ constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (p
 template <int NWK, int WI, bool DUMP, bool COUNT>
 static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
 {
-    const size_t lds = (size_t)NWK * 16 * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
+    const size_t lds = (size_t)(NWK * 16 + WI) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
     hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, DUMP, COUNT>), dim3(grid),
-                       dim3(WAVE * NWK * WI), lds, st, a.p, a.t_fast, a.blk_mm, a.sizes, a.cand,
+                       dim3(WAVE * NWK * WI), lds, st, a.p, a.recs, a.sizes, a.cand,
                        a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune, a.descending,
                        a.Fmin, a.Sbest, a.dummy_idx, a.F_all);
     return hipGetLastError();
@@ -288,7 +383,7 @@ hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, i
 // occupancy calculator.
 int fast_kernel_blocks_per_cu(int K)
 {
-    const size_t lds = (size_t)((K + 15) / 16) * 16 * WAVE * sizeof(int32_t);
+    const size_t lds = (size_t)(((K + 15) / 16) * 16 + 1) * WAVE * sizeof(int32_t);
     int nb = 0;
     hipError_t e;
     switch ((K + 15) / 16) {
