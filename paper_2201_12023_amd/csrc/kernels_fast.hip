@@ -17,12 +17,12 @@
 // Infinite entries need no filter: DEV_INF + anything >= DEV_INF and accumulators start at
 // DEV_INF.  Column loads (scalars and the LDS row) are issued one column ahead.
 //
-// Table layout (built once per handle by repack_fast_kernel): one record of KP + 16 int32
-// per column (s-1, q, i), columns in that order (i fastest), KP = 16 * ceil(K/16):
-//   rec[kp], kp = 0..KP-1    t_intra for first layer kp (0-based) and last layer i; DEV_INF
-//                            where kp > i, kp >= K or the entry is +infinity;
-//   rec[KP + 2 hb + {0,1}]   hb = 0..7: {min, max} over the finite entries of first layers
-//                            8hb..8hb+7 ({DEV_INF, DEV_INF} if there is none).
+// Table layout (built once per handle by repack_fast_kernel): one record per column
+// (s-1, q, i), columns in that order (i fastest); a record is KP/8 half-block entries of
+// HB_INTS = 10 int32 (KP = 16 * ceil(K/16)):
+//   {min, max over the finite t_intra of first layers 8hb..8hb+7 and last layer i
+//    ({DEV_INF, DEV_INF} if there is none), then the 8 values themselves: DEV_INF where the
+//    first layer is > i or >= K or the entry is +infinity}.
 // The array is padded by a few records so that the one-column-ahead loads may run past the
 // last column.
 #include "internal.hpp"
@@ -31,35 +31,35 @@ namespace alpa {
 
 typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-load path
 
+constexpr int HB_INTS = 10;
+
 __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int S, int KP,
                                    int32_t *__restrict__ recs)
 {
-    // one thread per (s, q, i, hb): fills 8 entries and their summary
-    const int REC = KP + 16;
-    const long long total = (long long)K * S * K * 8;
+    // one thread per (s, q, i, hb)
+    const int NHB = KP / 8;
+    const long long total = (long long)K * S * K * NHB;
     for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
          e += (long long)gridDim.x * blockDim.x) {
-        const int hb = (int)(e & 7);
-        long long r = e >> 3;
+        const int hb = (int)(e % NHB);
+        long long r = e / NHB;
         const int i = (int)(r % K); r /= K;
         const int q = (int)(r % S);
         const int s = (int)(r / S);
-        int32_t *rec = recs + (((long long)s * S + q) * K + i) * REC;
+        int32_t *rec = recs + ((((long long)s * S + q) * K + i) * NHB + hb) * HB_INTS;
         int32_t mn = DEV_INF, mx = -1;
-        if (8 * hb < KP) {
-            for (int u = 0; u < 8; ++u) {
-                const int k = 8 * hb + u;
-                int32_t v = DEV_INF;
-                if (k <= i && k < K) {
-                    const int32_t t = table[(((long long)s * K + k) * K + i) * S + q];
-                    if (t != INF_I32) v = t;
-                }
-                rec[k] = v;
-                if (v < DEV_INF) { mn = min(mn, v); mx = max(mx, v); }
+        for (int u = 0; u < 8; ++u) {
+            const int k = 8 * hb + u;
+            int32_t v = DEV_INF;
+            if (k <= i && k < K) {
+                const int32_t t = table[(((long long)s * K + k) * K + i) * S + q];
+                if (t != INF_I32) v = t;
             }
+            rec[2 + u] = v;
+            if (v < DEV_INF) { mn = min(mn, v); mx = max(mx, v); }
         }
-        rec[KP + 2 * hb + 0] = mn;
-        rec[KP + 2 * hb + 1] = (mx < 0) ? DEV_INF : mx;
+        rec[0] = mn;
+        rec[1] = (mx < 0) ? DEV_INF : mx;
     }
 }
 
@@ -69,12 +69,12 @@ struct HalfColumn {
     int32_t mn, mx;            // the half-block's min / max over finite entries
 };
 
-__device__ __forceinline__ void load_half(HalfColumn &h, cptr_t tp, cptr_t mm)
+__device__ __forceinline__ void load_half(HalfColumn &h, cptr_t rec)
 {
+    h.mn = rec[0];
+    h.mx = rec[1];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) h.t[u] = tp[u];
-    h.mn = mm[0];
-    h.mx = mm[1];
+    for (int u = 0; u < 8; ++u) h.t[u] = rec[2 + u];
 }
 
 // Makes loaded values "used" here, so that the wait for them is placed before the next
@@ -100,14 +100,15 @@ template <bool COUNT>
 __device__ __forceinline__ void relax8(int32_t *acc, int32_t (&t)[8], int32_t mn, int32_t mx,
                                        int32_t G, int32_t c, unsigned &n_blocks)
 {
-    if (mx > c) {
-        if (mn > c) return;                   // nothing in the half-block passes the filter
+    if (mn <= c) {                            // else nothing in the half-block passes
+        if (mx > c) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c) ? t[u] : DEV_INF;
+            for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c) ? t[u] : DEV_INF;
+        }
+        if (COUNT) ++n_blocks;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u] = min(acc[u], t[u] + G);
     }
-    if (COUNT) ++n_blocks;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc[u] = min(acc[u], t[u] + G);
 }
 
 // Lower-index evidence for the pruning rule (see recurrence_generic_kernel).
@@ -146,10 +147,8 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     const int rowA = 8 * hbA, rowB = 8 * hbB;
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
-    constexpr int REC = KP + 16;                       // int32 per column record
+    constexpr int REC = (KP / 8) * HB_INTS;            // int32 per column record
     const cptr_t recs = (cptr_t)recs_g;
-    const int oA = rowA, oB = rowB;                    // record offsets of the wave's operands
-    const int omA = KP + 2 * hbA, omB = KP + 2 * hbB;
     const cptr_t sizes = (cptr_t)sizes_g;
     int32_t *Fprev = lds;
     int32_t *Fnext = lds + (KP + WI) * WAVE;
@@ -201,16 +200,18 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 const int a = sizes[q];
                 if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
                 if (i0 > i_hi) continue;
-                cptr_t rec = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
-                const cptr_t rec_last = rec + (size_t)(i_hi - i0) * REC;
+                constexpr int STEP = REC * WI;
+                const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
+                cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
+                const int ncol = (i_hi - i0) / WI + 1;         // columns of this wave
                 HalfColumn hA, hB;
                 if (s == 1) {
                     // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
                     const int32_t G = (lane + 1 == a) ? 0 : DEV_INF;
                     int i = i0;
-                    for (; rec <= rec_last; rec += REC * WI, i += WI) {
-                        load_half(hA, rec + oA, rec + omA);
-                        load_half(hB, rec + oB, rec + omB);
+                    for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, i += WI) {
+                        load_half(hA, pA);
+                        load_half(hB, pB);
                         relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
                         if (i >= rowB) relax8<COUNT>(acc + 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                     }
@@ -223,48 +224,51 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 const bool live = lane >= a;           // d - a_q >= 1
                 const int32_t *frow = Fprev + (live ? lane - a : 0) + (i0 + 1) * WAVE;   // row i+1
                 int32_t f = *frow;
-                load_half(hA, rec + oA, rec + omA);
+                load_half(hA, pA);
                 fence_loads();
                 // columns that only reach half-block A, two per trip (hB serves as the
                 // second buffer); an odd one is done without overlap
-                constexpr int STEP = REC * WI;
-                int n1 = min((rowB - i0 + WI - 1) / WI, (i_hi - i0) / WI + 1);
-                for (; n1 >= 2; n1 -= 2, rec += 2 * STEP) {
+                const int n1 = max(0, min((rowB - i0 + WI - 1) / WI, ncol));
+                for (int x = n1 >> 1; x > 0; --x) {
                     settle(hA, f);
                     frow += WAVE * WI;
                     int32_t f2 = *frow;
-                    load_half(hB, rec + STEP + oA, rec + STEP + omA);
+                    load_half(hB, pA + STEP);
                     fence_loads();
                     const int32_t G = live ? f : DEV_INF;
                     relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
                     settle(hB, f2);
                     frow += WAVE * WI;
                     f = *frow;
-                    load_half(hA, rec + 2 * STEP + oA, rec + 2 * STEP + omA);
+                    pA += 2 * STEP;
+                    load_half(hA, pA);
                     fence_loads();
                     const int32_t G2 = live ? f2 : DEV_INF;
                     relax8<COUNT>(acc, hB.t, hB.mn, hB.mx, G2, c, n_blocks);
                 }
-                if (n1 == 1) {
+                if (n1 & 1) {
                     const int32_t G = live ? f : DEV_INF;
                     relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
-                    rec += STEP;
+                    pA += STEP;
                     frow += WAVE * WI;
                     f = *frow;
-                    load_half(hA, rec + oA, rec + omA);
+                    load_half(hA, pA);
                     fence_loads();
                 }
                 // columns that reach both half-blocks
-                for (; rec <= rec_last; rec += STEP) {
+                pB += (size_t)n1 * STEP;
+                for (int x = ncol - n1; x > 0; --x) {
                     settle(hA, f);
-                    load_half(hB, rec + oB, rec + omB);
+                    load_half(hB, pB);
                     fence_loads();
                     const int32_t G = live ? f : DEV_INF;
                     relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
                     settle(hB);
                     frow += WAVE * WI;
                     f = *frow;
-                    load_half(hA, rec + STEP + oA, rec + STEP + omA);
+                    pA += STEP;
+                    pB += STEP;
+                    load_half(hA, pA);
                     fence_loads();
                     relax8<COUNT>(acc + 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                 }
@@ -332,7 +336,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
                               int32_t *recs)
 {
-    long long total = (long long)K * K * S * 8;
+    long long total = (long long)K * K * S * (KP / 8);
     int grid = (int)((total + 255) / 256);
     if (grid > 8192) grid = 8192;
     hipLaunchKernelGGL(repack_fast_kernel, dim3(grid), dim3(256), 0, st, table, K, S, KP, recs);
@@ -342,7 +346,7 @@ hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S
 size_t fast_table_ints(int K, int S)
 {
     const int KP = 16 * ((K + 15) / 16);
-    return ((size_t)K * S * K + 8) * (size_t)(KP + 16);     // 8 records of padding
+    return ((size_t)K * S * K + 8) * (size_t)((KP / 8) * HB_INTS);     // 8 records of padding
 }
 
 constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (plan) run
