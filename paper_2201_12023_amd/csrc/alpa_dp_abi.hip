@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -41,7 +42,7 @@ struct alpa_dp {
     int n_cu = 0;
     bool fast_ok = false;
     int KP = 0;
-    int fast_grid_max = 0, generic_grid_max = 0;
+    int fast_grid_max[3] = {0, 0, 0}, generic_grid_max = 0;   // [nc] for nc = 1, 2
 
     int32_t *d_table = nullptr, *d_sizes = nullptr, *d_recs = nullptr;
     PrepBuffers pb{};
@@ -207,9 +208,15 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
             HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
             HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
             HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
-            const int per_cu = fast_kernel_blocks_per_cu(K);
-            if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
-            h->fast_grid_max = h->n_cu * per_cu;
+            for (int nc = 1; nc <= 2; ++nc) {
+                int per_cu = fast_kernel_blocks_per_cu(K, nc);
+                if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
+                if (const char *e = getenv("ALPA_DP_WG_PER_CU")) {   // tuning aid
+                    const int v = atoi(e);
+                    if (v >= 1 && v < per_cu) per_cu = v;
+                }
+                h->fast_grid_max[nc] = h->n_cu * per_cu;
+            }
         }
         int rc2 = alloc_candidate_arrays(h, std::max(h->n_table_keys, 1024));
         if (rc2) return rc2;
@@ -306,13 +313,17 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (bound > 0) {
         const bool fast = h->fast_ok && !(flags & ALPA_DP_GENERIC);
         if (fast) {
-            const int grid = std::max(1, std::min(bound, h->fast_grid_max));
+            // two candidates per workgroup share every scalar load; worth it once there are
+            // enough candidates to fill the device twice over that way
+            int nc = (bound >= 4 * h->fast_grid_max[2]) ? 2 : 1;
+            if (const char *e = getenv("ALPA_DP_NC")) nc = atoi(e) == 2 ? 2 : 1;   // tuning aid
+            const int grid = std::max(1, std::min((bound + nc - 1) / nc, h->fast_grid_max[nc]));
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
                         /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr};
             HIPCHK(launch_recurrence_fast(st, fa, (flags & ALPA_DP_COUNT_WORK) ? FAST_MODE_COUNT
                                                                               : FAST_MODE_BATCH,
-                                          grid));
+                                          nc, grid));
         } else {
             const int grid = std::max(1, std::min(bound, h->generic_grid_max));
             HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, h->d_cand,
@@ -331,7 +342,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         FastArgs fa{p, h->d_recs, h->d_sizes, &h->d_state->best_c,
                     &h->d_state->plan_n, &h->d_state->plan_ticket, &h->d_state->wave_relax,
                     nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall};
-        HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1));
+        HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1, 1));
     } else {
         HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, &h->d_state->best_c,
                                          &h->d_state->plan_n, &h->d_state->plan_ticket, nullptr, 0,

@@ -147,8 +147,8 @@ struct FastArgs {
     int32_t *F_all;          // [Smax+1][(K+2)*(D+1)], plan mode only
 };
 enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
-hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int grid);
-int fast_kernel_blocks_per_cu(int K);
+hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);
+int fast_kernel_blocks_per_cu(int K, int nc);
 
 hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand,
                            const int32_t *Fmin, const int32_t *Sbest, SolveState *state, int prune,

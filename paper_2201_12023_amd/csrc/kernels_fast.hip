@@ -94,20 +94,36 @@ __device__ __forceinline__ void settle(const HalfColumn &h, int32_t f)
 }
 __device__ __forceinline__ void fence_loads() { asm volatile("" ::: "memory"); }
 
-// Eight first layers against one column: unfiltered when every finite entry passes, skipped
-// when none does, else filtered entry by entry on the scalar unit.
-template <bool COUNT>
-__device__ __forceinline__ void relax8(int32_t *acc, int32_t (&t)[8], int32_t mn, int32_t mx,
-                                       int32_t G, int32_t c, unsigned &n_blocks)
+// Eight first layers against one column, for the NC candidates of the workgroup (ascending:
+// c[0] <= c[1] <= ...).  A half-block is skipped when none of its entries passes the largest
+// candidate, taken unfiltered when every finite entry passes the smallest, else filtered on
+// the scalar unit candidate by candidate, from the largest down (the filtered set only
+// shrinks, so the filter is applied in place).
+template <int NC, bool COUNT>
+__device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)[8], int32_t mn,
+                                       int32_t mx, const int32_t (&G)[NC], const int32_t (&c)[NC],
+                                       unsigned &n_blocks)
 {
-    if (mn <= c) {                            // else nothing in the half-block passes
-        if (mx > c) {
+    if (mn <= c[NC - 1]) {                    // else nothing passes even the largest candidate
+        int32_t te[NC][8];                    // per-candidate scalar operands
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c) ? t[u] : DEV_INF;
+        for (int e = 0; e < NC; ++e)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) te[e][u] = t[u];
+        if (mx > c[0]) {                      // some candidate needs the entry-wise filter
+#pragma unroll
+            for (int e = NC - 1; e >= 0; --e)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int32_t src = (e == NC - 1) ? t[u] : te[e + 1][u];
+                    te[e][u] = (src <= c[e]) ? src : DEV_INF;
+                }
         }
-        if (COUNT) ++n_blocks;
+        if (COUNT) n_blocks += NC;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc[u] = min(acc[u], t[u] + G);
+        for (int e = 0; e < NC; ++e)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[e][off + u] = min(acc[e][off + u], te[e][u] + G[e]);
     }
 }
 
@@ -124,19 +140,22 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 }
 
 // NWK = waves along the first-layer axis (= ceil(K / 16)); WI = waves along the column
-// axis; DUMP = also store every layer to F_all (plan recovery); COUNT = tally executed
-// blocks.  Fmin / Sbest have a spare slot at index dummy_idx for the waves that do not
-// own the result.
-template <int NWK, int WI, bool DUMP, bool COUNT>
+// axis; NC = candidates evaluated together by one workgroup (they share every scalar load);
+// DUMP = also store every layer to F_all (plan recovery, NC = 1); COUNT = tally executed
+// half-blocks.  Fmin / Sbest have a spare slot at index dummy_idx for results nobody owns.
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
 __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
-    Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g, const int32_t *__restrict__ cand,
-    const int32_t *__restrict__ n_cand_p, int32_t *ticket, unsigned long long *wave_relax,
-    int64_t *chunk_min, int prune, int descending, int32_t *__restrict__ Fmin,
-    int32_t *__restrict__ Sbest, int dummy_idx, int32_t *__restrict__ F_all)
+    Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g,
+    const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
+    unsigned long long *wave_relax, int64_t *chunk_min, int prune, int descending,
+    int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest, int dummy_idx,
+    int32_t *__restrict__ F_all)
 {
+    static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
-    extern __shared__ int32_t lds[];                   // Fprev [KP+WI][64] (+ Fnext, same size)
+    constexpr int ROWS = KP + WI;                      // LDS rows per F layer (+ read-ahead slack)
+    extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
     __shared__ int32_t sh_tk[NT];
     __shared__ int32_t sh_skip[NWK * WI];
     const int tid = threadIdx.x;
@@ -151,8 +170,9 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     const cptr_t recs = (cptr_t)recs_g;
     const cptr_t sizes = (cptr_t)sizes_g;
     int32_t *Fprev = lds;
-    int32_t *Fnext = lds + (KP + WI) * WAVE;
+    int32_t *Fnext = lds + NC * ROWS * WAVE;
     const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
+    const int n_groups = (n + NC - 1) / NC;
     unsigned long long n_blocks_total = 0;
 
     for (;;) {
@@ -164,18 +184,29 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
         __syncthreads();
         const int tk = __builtin_amdgcn_readfirstlane(sh_tk[0]);
         __syncthreads();
-        if (tk >= n) break;                            // the workgroup's only exit
-        const int j = descending ? (n - 1 - tk) : tk;
-        const int32_t c = __builtin_amdgcn_readfirstlane(cand[j]);
+        if (tk >= n_groups) break;                     // the workgroup's only exit
+        const int j0 = (descending ? (n_groups - 1 - tk) : tk) * NC;
+        int jj[NC];                                    // candidate indices (the last may repeat)
+        int32_t c[NC];
+#pragma unroll
+        for (int e = 0; e < NC; ++e) {
+            jj[e] = min(j0 + e, n - 1);
+            c[e] = __builtin_amdgcn_readfirstlane(cand[jj[e]]);
+        }
         if (prune) {
-            // wave 0's reading of the published minima decides for the whole workgroup
-            sh_skip[wid] = can_skip_fast(chunk_min, j, c, p.B, lane) ? 1 : 0;
+            // If the lowest candidate of the group may be skipped so may the others (their
+            // evidence set is a superset and B * t_max is larger).  Wave 0's reading of the
+            // published minima decides for the whole workgroup.
+            sh_skip[wid] = can_skip_fast(chunk_min, jj[0], c[0], p.B, lane) ? 1 : 0;
             __syncthreads();
             const int skip = __builtin_amdgcn_readfirstlane(sh_skip[0]);
             __syncthreads();
             if (skip) {
-                Fmin[j] = DEV_INF;                     // all threads, same value
-                Sbest[j] = -1;
+#pragma unroll
+                for (int e = 0; e < NC; ++e) {
+                    Fmin[jj[e]] = DEV_INF;             // all threads, same value
+                    Sbest[jj[e]] = -1;
+                }
                 continue;
             }
         }
@@ -184,17 +215,21 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
             for (int x = tid; x < total; x += NT) F_all[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
             __syncthreads();
         }
-        int32_t best = DEV_INF, sbest = 0;
+        int32_t best[NC], sbest[NC];
+#pragma unroll
+        for (int e = 0; e < NC; ++e) { best[e] = DEV_INF; sbest[e] = 0; }
         unsigned n_blocks = 0;
         for (int s = 1; s <= p.Smax; ++s) {
-            int32_t acc[16];                           // [0..7] half-block A, [8..15] half-block B
+            int32_t acc[NC][16];                       // [0..7] half-block A, [8..15] half-block B
 #pragma unroll
-            for (int u = 0; u < 16; ++u) acc[u] = DEV_INF;
+            for (int e = 0; e < NC; ++e)
+#pragma unroll
+                for (int u = 0; u < 16; ++u) acc[e][u] = DEV_INF;
             const int i_lo = (s == 1) ? K - 1 : 0;     // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
             const int i0 = max(i_lo, rowA) + wi;       // columns that reach half-block A
             if (WI > 1) {
-                for (int x = tid; x < (KP + WI) * WAVE; x += NT) Fnext[x] = DEV_INF;
+                for (int x = tid; x < NC * ROWS * WAVE; x += NT) Fnext[x] = DEV_INF;
             }
             for (int q = 0; q < S; ++q) {
                 const int a = sizes[q];
@@ -205,95 +240,114 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
                 const int ncol = (i_hi - i0) / WI + 1;         // columns of this wave
                 HalfColumn hA, hB;
+                int32_t G[NC];
                 if (s == 1) {
                     // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
-                    const int32_t G = (lane + 1 == a) ? 0 : DEV_INF;
+#pragma unroll
+                    for (int e = 0; e < NC; ++e) G[e] = (lane + 1 == a) ? 0 : DEV_INF;
                     int i = i0;
                     for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, i += WI) {
                         load_half(hA, pA);
                         load_half(hB, pB);
-                        relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
-                        if (i >= rowB) relax8<COUNT>(acc + 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
+                        relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                        if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                     }
                     continue;
                 }
                 // Pipeline, one step ahead: while half-block A of a column is computed the
                 // loads for its half-block B are in flight, and while B is computed the loads
-                // for A of the next column (and that column's LDS row) are.  The loads after
+                // for A of the next column (and that column's LDS rows) are.  The loads after
                 // the last column land in the padding and are dropped.
                 const bool live = lane >= a;           // d - a_q >= 1
                 const int32_t *frow = Fprev + (live ? lane - a : 0) + (i0 + 1) * WAVE;   // row i+1
-                int32_t f = *frow;
+                int32_t f[NC], f2[NC];
+                auto load_rows = [&](int32_t (&dst)[NC]) {
+#pragma unroll
+                    for (int e = 0; e < NC; ++e) dst[e] = frow[e * ROWS * WAVE];
+                };
+                auto operands = [&](const int32_t (&src)[NC]) {
+#pragma unroll
+                    for (int e = 0; e < NC; ++e) G[e] = live ? src[e] : DEV_INF;
+                };
+                load_rows(f);
                 load_half(hA, pA);
                 fence_loads();
                 // columns that only reach half-block A, two per trip (hB serves as the
                 // second buffer); an odd one is done without overlap
                 const int n1 = max(0, min((rowB - i0 + WI - 1) / WI, ncol));
                 for (int x = n1 >> 1; x > 0; --x) {
-                    settle(hA, f);
+                    settle(hA, f[0]);
                     frow += WAVE * WI;
-                    int32_t f2 = *frow;
+                    load_rows(f2);
                     load_half(hB, pA + STEP);
                     fence_loads();
-                    const int32_t G = live ? f : DEV_INF;
-                    relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
-                    settle(hB, f2);
+                    operands(f);
+                    relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                    settle(hB, f2[0]);
                     frow += WAVE * WI;
-                    f = *frow;
+                    load_rows(f);
                     pA += 2 * STEP;
                     load_half(hA, pA);
                     fence_loads();
-                    const int32_t G2 = live ? f2 : DEV_INF;
-                    relax8<COUNT>(acc, hB.t, hB.mn, hB.mx, G2, c, n_blocks);
+                    operands(f2);
+                    relax8<NC, COUNT>(acc, 0, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                 }
                 if (n1 & 1) {
-                    const int32_t G = live ? f : DEV_INF;
-                    relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                    operands(f);
+                    relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
                     pA += STEP;
                     frow += WAVE * WI;
-                    f = *frow;
+                    load_rows(f);
                     load_half(hA, pA);
                     fence_loads();
                 }
                 // columns that reach both half-blocks
                 pB += (size_t)n1 * STEP;
                 for (int x = ncol - n1; x > 0; --x) {
-                    settle(hA, f);
+                    settle(hA, f[0]);
                     load_half(hB, pB);
                     fence_loads();
-                    const int32_t G = live ? f : DEV_INF;
-                    relax8<COUNT>(acc, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                    operands(f);
+                    relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
                     settle(hB);
                     frow += WAVE * WI;
-                    f = *frow;
+                    load_rows(f);
                     pA += STEP;
                     pB += STEP;
                     load_half(hA, pA);
                     fence_loads();
-                    relax8<COUNT>(acc + 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
                 }
             }
             __syncthreads();                           // every wave is done reading Fprev
-            int32_t f1;
+            int32_t f1[NC];
             if (WI == 1) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {          // rows 0 and >= K are never operands
-                    Fprev[(rowA + u) * WAVE + lane] = acc[u];
-                    Fprev[(rowB + u) * WAVE + lane] = acc[8 + u];
-                }
+                for (int e = 0; e < NC; ++e)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {      // rows 0 and >= K are never operands
+                        Fprev[(e * ROWS + rowA + u) * WAVE + lane] = acc[e][u];
+                        Fprev[(e * ROWS + rowB + u) * WAVE + lane] = acc[e][8 + u];
+                    }
                 __syncthreads();
-                f1 = acc[0];                           // F(s, first layer, .) in wave 0 (half-block 0)
+#pragma unroll
+                for (int e = 0; e < NC; ++e) f1[e] = acc[e][0];   // F(s, first layer, .) in wave 0
             } else {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    atomicMin(&Fnext[(rowA + u) * WAVE + lane], acc[u]);
-                    atomicMin(&Fnext[(rowB + u) * WAVE + lane], acc[8 + u]);
-                }
+                for (int e = 0; e < NC; ++e)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        atomicMin(&Fnext[(e * ROWS + rowA + u) * WAVE + lane], acc[e][u]);
+                        atomicMin(&Fnext[(e * ROWS + rowB + u) * WAVE + lane], acc[e][8 + u]);
+                    }
                 __syncthreads();
                 int32_t *tmp = Fprev; Fprev = Fnext; Fnext = tmp;
-                f1 = Fprev[lane];                      // row 0 holds F(s, first layer, .)
+#pragma unroll
+                for (int e = 0; e < NC; ++e) f1[e] = Fprev[e * ROWS * WAVE + lane];   // row 0
             }
-            if (f1 < best) { best = f1; sbest = s; }   // lowest s on ties
+#pragma unroll
+            for (int e = 0; e < NC; ++e)
+                if (f1[e] < best[e]) { best[e] = f1[e]; sbest[e] = s; }   // lowest s on ties
             if (DUMP) {
                 int32_t *Fs = F_all + (size_t)s * LS;
                 if (WI == 1) {
@@ -301,7 +355,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                     for (int u = 0; u < 16; ++u) {
                         const int k = (u < 8 ? rowA : rowB - 8) + u;
                         const bool in = lane < D;
-                        if (k < K) Fs[(k + 1) * (D + 1) + (in ? lane + 1 : 0)] = in ? acc[u] : DEV_INF;
+                        if (k < K) Fs[(k + 1) * (D + 1) + (in ? lane + 1 : 0)] = in ? acc[0][u] : DEV_INF;
                     }
                 } else {
                     // lanes beyond the mesh rewrite the row's d = 0 cell with infinity
@@ -314,21 +368,25 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 }
             }
         }
-        // lane D-1 holds F(s, first layer, all devices); wave 0 owns the result
-        const int32_t bestD = __builtin_amdgcn_readlane(best, D - 1);
-        const int32_t sD = __builtin_amdgcn_readlane(sbest, D - 1);
-        const bool owner = (wid == 0);
-        const int slot = owner ? j : dummy_idx;
-        Fmin[slot] = bestD;                            // all lanes, same value
-        Sbest[slot] = bestD >= DEV_INF ? 0 : sD;
-        if (prune) {                                   // uniform; the minimum is idempotent
-            const long long T = (owner && bestD < DEV_INF)
-                                    ? (long long)bestD + (long long)(p.B - 1) * (long long)c
-                                    : (long long)INF_I64;
-            atomicMin((long long *)&chunk_min[j / PRUNE_CHUNK], T);
+        // lane D-1 holds F(s, first layer, all devices); wave 0 owns the results; a repeated
+        // last candidate goes to the spare slot
+#pragma unroll
+        for (int e = 0; e < NC; ++e) {
+            const int32_t bestD = __builtin_amdgcn_readlane(best[e], D - 1);
+            const int32_t sD = __builtin_amdgcn_readlane(sbest[e], D - 1);
+            const bool owner = (wid == 0) && (j0 + e < n);
+            const int slot = owner ? jj[e] : dummy_idx;
+            Fmin[slot] = bestD;                        // all lanes, same value
+            Sbest[slot] = bestD >= DEV_INF ? 0 : sD;
+            if (prune) {                               // uniform; the minimum is idempotent
+                const long long T = (owner && bestD < DEV_INF)
+                                        ? (long long)bestD + (long long)(p.B - 1) * (long long)c[e]
+                                        : (long long)INF_I64;
+                atomicMin((long long *)&chunk_min[jj[e] / PRUNE_CHUNK], T);
+            }
         }
         if (COUNT) n_blocks_total += n_blocks;
-        __syncthreads();                               // LDS is reused by the next candidate
+        __syncthreads();                               // LDS is reused by the next group
     }
     if (COUNT) atomicAdd(wave_relax, lane == 0 ? n_blocks_total * 8ull : 0ull);
 }
@@ -351,57 +409,69 @@ size_t fast_table_ints(int K, int S)
 
 constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (plan) run
 
-template <int NWK, int WI, bool DUMP, bool COUNT>
+template <int NWK, int WI, int NC>
+static size_t fast_lds_bytes()
+{
+    return (size_t)NC * (NWK * 16 + WI) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
+}
+
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
 static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
 {
-    const size_t lds = (size_t)(NWK * 16 + WI) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
-    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, DUMP, COUNT>), dim3(grid),
-                       dim3(WAVE * NWK * WI), lds, st, a.p, a.recs, a.sizes, a.cand,
-                       a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune, a.descending,
-                       a.Fmin, a.Sbest, a.dummy_idx, a.F_all);
+    const size_t lds = fast_lds_bytes<NWK, WI, NC>();
+    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>), dim3(grid),
+                       dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
+                       a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
+                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all);
     return hipGetLastError();
 }
 
 template <int NWK>
-static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int grid)
+static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc, int grid)
 {
     switch (mode) {
-    case FAST_MODE_PLAN: return launch_one<NWK, PLAN_WI, true, false>(st, a, grid);
-    case FAST_MODE_COUNT: return launch_one<NWK, 1, false, true>(st, a, grid);
-    default: return launch_one<NWK, 1, false, false>(st, a, grid);
+    case FAST_MODE_PLAN: return launch_one<NWK, PLAN_WI, 1, true, false>(st, a, grid);
+    case FAST_MODE_COUNT:
+        return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
+                       : launch_one<NWK, 1, 1, false, true>(st, a, grid);
+    default:
+        return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
+                       : launch_one<NWK, 1, 1, false, false>(st, a, grid);
     }
 }
 
-hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int grid)
+// nc = candidates per workgroup (1 or 2); grid = persistent workgroups
+hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid)
 {
     switch ((a.p.K + 15) / 16) {
-    case 1: return launch_nwk<1>(st, a, mode, grid);
-    case 2: return launch_nwk<2>(st, a, mode, grid);
-    case 3: return launch_nwk<3>(st, a, mode, grid);
-    case 4: return launch_nwk<4>(st, a, mode, grid);
+    case 1: return launch_nwk<1>(st, a, mode, nc, grid);
+    case 2: return launch_nwk<2>(st, a, mode, nc, grid);
+    case 3: return launch_nwk<3>(st, a, mode, nc, grid);
+    case 4: return launch_nwk<4>(st, a, mode, nc, grid);
     default: return hipErrorInvalidValue;
     }
 }
 
-// Resident workgroups of the batch-mode kernel per compute unit, from the runtime's
-// occupancy calculator.
-int fast_kernel_blocks_per_cu(int K)
+template <int NWK, int NC>
+static int blocks_per_cu()
 {
-    const size_t lds = (size_t)(((K + 15) / 16) * 16 + 1) * WAVE * sizeof(int32_t);
     int nb = 0;
-    hipError_t e;
+    const size_t lds = fast_lds_bytes<NWK, 1, NC>();
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+        &nb, recurrence_fast_kernel<NWK, 1, NC, false, false>, WAVE * NWK, lds);
+    return e == hipSuccess ? nb : 0;
+}
+
+// Resident workgroups of the batch-mode kernel per compute unit for nc candidates per
+// workgroup, from the runtime's occupancy calculator.
+int fast_kernel_blocks_per_cu(int K, int nc)
+{
     switch ((K + 15) / 16) {
-    case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &nb, recurrence_fast_kernel<1, 1, false, false>, WAVE * 1, lds); break;
-    case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &nb, recurrence_fast_kernel<2, 1, false, false>, WAVE * 2, lds); break;
-    case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &nb, recurrence_fast_kernel<3, 1, false, false>, WAVE * 3, lds); break;
-    default: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &nb, recurrence_fast_kernel<4, 1, false, false>, WAVE * 4, lds); break;
+    case 1: return nc == 2 ? blocks_per_cu<1, 2>() : blocks_per_cu<1, 1>();
+    case 2: return nc == 2 ? blocks_per_cu<2, 2>() : blocks_per_cu<2, 1>();
+    case 3: return nc == 2 ? blocks_per_cu<3, 2>() : blocks_per_cu<3, 1>();
+    default: return nc == 2 ? blocks_per_cu<4, 2>() : blocks_per_cu<4, 1>();
     }
-    if (e != hipSuccess) return 0;
-    return nb;
 }
 
 }  // namespace alpa
