@@ -30,6 +30,12 @@ def main():
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=48)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times, so that a counter "
+                         "run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="measured HBM bytes per launch of the recurrence kernel (from a "
+                         "rocprofv3 --pmc run, see profiles/), reported as roofline.traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over t_max candidates; "
@@ -64,6 +70,13 @@ def main():
     def step():
         B.alpa_dp_solve_dev(h, None, nq, flags, d_T, d_plan)
 
+    if args.copy_calibration:
+        with torch.cuda.stream(stream):
+            src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.int32, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+        stream.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -116,7 +129,7 @@ def main():
                                f"prune {'on' if w.prune else 'off'}, seed {w.seed}"},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12,
                      "unit": "Tlane-op/s (int32)", "frac": achieved / INT32_VALU_PEAK,
-                     "traffic": None, "kernel": "recurrence_fast_kernel",
+                     "traffic": args.traffic_bytes, "kernel": "recurrence_fast_kernel",
                      "kernel_ms_avg": rec_avg},
         "extra": {"candidates_per_s": C / (dt / args.steps),
                   "cell_updates_per_s_alg1_dense": wc["n_dense"] * C / (dt / args.steps),
