@@ -105,25 +105,26 @@ __device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)
                                        unsigned &n_blocks)
 {
     if (mn <= c[NC - 1]) {                    // else nothing passes even the largest candidate
-        int32_t te[NC][8];                    // per-candidate scalar operands
 #pragma unroll
-        for (int e = 0; e < NC; ++e)
+        for (int e = NC - 1; e >= 0; --e) {   // largest candidate first: the filter only shrinks
+            if (mx > c[e]) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) te[e][u] = t[u];
-        if (mx > c[0]) {                      // some candidate needs the entry-wise filter
+                for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[e]) ? t[u] : DEV_INF;
+            }
+            if (COUNT) ++n_blocks;
 #pragma unroll
-            for (int e = NC - 1; e >= 0; --e)
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int32_t src = (e == NC - 1) ? t[u] : te[e + 1][u];
-                    te[e][u] = (src <= c[e]) ? src : DEV_INF;
-                }
+            for (int u = 0; u < 8; ++u) acc[e][off + u] = min(acc[e][off + u], t[u] + G[e]);
+            // The next candidate filters the same eight registers in place; pinning them here
+            // keeps the two update sequences apart (merged, they need a second copy of the
+            // values, i.e. eight scalar moves per half-block).
+            if (e > 0)
+                asm volatile("" : "+s"(t[0]), "+s"(t[1]), "+s"(t[2]), "+s"(t[3]), "+s"(t[4]),
+                                  "+s"(t[5]), "+s"(t[6]), "+s"(t[7]), "+v"(acc[e][off + 0]),
+                                  "+v"(acc[e][off + 1]), "+v"(acc[e][off + 2]),
+                                  "+v"(acc[e][off + 3]), "+v"(acc[e][off + 4]),
+                                  "+v"(acc[e][off + 5]), "+v"(acc[e][off + 6]),
+                                  "+v"(acc[e][off + 7]));
         }
-        if (COUNT) n_blocks += NC;
-#pragma unroll
-        for (int e = 0; e < NC; ++e)
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc[e][off + u] = min(acc[e][off + u], te[e][u] + G[e]);
     }
 }
 
