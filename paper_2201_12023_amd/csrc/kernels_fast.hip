@@ -155,7 +155,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
-    constexpr int ROWS = KP + WI;                      // LDS rows per F layer (+ read-ahead slack)
+    constexpr int ROWS = KP + 6 * WI;                  // LDS rows per F layer (+ read-ahead slack)
     extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
     __shared__ int32_t sh_tk[NT];
     __shared__ int32_t sh_skip[NWK * WI];
@@ -255,69 +255,106 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                     }
                     continue;
                 }
-                // Pipeline, one step ahead: while half-block A of a column is computed the
-                // loads for its half-block B are in flight, and while B is computed the loads
-                // for A of the next column (and that column's LDS rows) are.  The loads after
+                // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
+                // their LDS rows; while one batch is computed the loads of the next are in
+                // flight, so every wait is covered by a whole batch of updates.  Where only
+                // half-block A is reached (last layer < rowB) a batch is the A halves of two
+                // columns, afterwards it is the A and B halves of one column.  Loads past
                 // the last column land in the padding and are dropped.
                 const bool live = lane >= a;           // d - a_q >= 1
                 const int32_t *frow = Fprev + (live ? lane - a : 0) + (i0 + 1) * WAVE;   // row i+1
-                int32_t f[NC], f2[NC];
-                auto load_rows = [&](int32_t (&dst)[NC]) {
+                struct Batch { HalfColumn X, Y; int32_t fX[NC], fY[NC]; } b0, b1;
+                auto rows = [&](int32_t (&dst)[NC], int col) {     // col: columns ahead of frow
 #pragma unroll
-                    for (int e = 0; e < NC; ++e) dst[e] = frow[e * ROWS * WAVE];
+                    for (int e = 0; e < NC; ++e) dst[e] = frow[(e * ROWS + col * WI) * WAVE];
                 };
                 auto operands = [&](const int32_t (&src)[NC]) {
 #pragma unroll
                     for (int e = 0; e < NC; ++e) G[e] = live ? src[e] : DEV_INF;
                 };
-                load_rows(f);
-                load_half(hA, pA);
-                fence_loads();
-                // columns that only reach half-block A, two per trip (hB serves as the
-                // second buffer); an odd one is done without overlap
+                auto settle_batch = [&](const Batch &b) {
+                    settle(b.X, b.fX[0]);
+                    settle(b.Y, b.fY[0]);
+                };
+                // --- columns that only reach half-block A: slots = columns i and i + WI
+                auto load_AA = [&](Batch &b, int col) {
+                    rows(b.fX, col);
+                    rows(b.fY, col + 1);
+                    load_half(b.X, pA + (size_t)col * STEP);
+                    load_half(b.Y, pA + (size_t)(col + 1) * STEP);
+                    fence_loads();
+                };
+                auto compute_AA = [&](Batch &b) {
+                    operands(b.fX);
+                    relax8<NC, COUNT>(acc, 0, b.X.t, b.X.mn, b.X.mx, G, c, n_blocks);
+                    operands(b.fY);
+                    relax8<NC, COUNT>(acc, 0, b.Y.t, b.Y.mn, b.Y.mx, G, c, n_blocks);
+                };
                 const int n1 = max(0, min((rowB - i0 + WI - 1) / WI, ncol));
-                for (int x = n1 >> 1; x > 0; --x) {
-                    settle(hA, f[0]);
-                    frow += WAVE * WI;
-                    load_rows(f2);
-                    load_half(hB, pA + STEP);
-                    fence_loads();
-                    operands(f);
-                    relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
-                    settle(hB, f2[0]);
-                    frow += WAVE * WI;
-                    load_rows(f);
-                    pA += 2 * STEP;
-                    load_half(hA, pA);
-                    fence_loads();
-                    operands(f2);
-                    relax8<NC, COUNT>(acc, 0, hB.t, hB.mn, hB.mx, G, c, n_blocks);
+                int left = n1;
+                if (left >= 2) {
+                    load_AA(b0, 0);
+                    for (; left >= 4; left -= 4) {
+                        settle_batch(b0);
+                        load_AA(b1, 2);
+                        compute_AA(b0);
+                        settle_batch(b1);
+                        load_AA(b0, 4);
+                        compute_AA(b1);
+                        pA += 4 * STEP;
+                        frow += 4 * WI * WAVE;
+                    }
+                    if (left >= 2) {
+                        settle_batch(b0);
+                        compute_AA(b0);
+                        pA += 2 * STEP;
+                        frow += 2 * WI * WAVE;
+                        left -= 2;
+                    }
                 }
-                if (n1 & 1) {
-                    operands(f);
-                    relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
+                if (left == 1) {
+                    rows(b0.fX, 0);
+                    load_half(b0.X, pA);
+                    operands(b0.fX);
+                    relax8<NC, COUNT>(acc, 0, b0.X.t, b0.X.mn, b0.X.mx, G, c, n_blocks);
                     pA += STEP;
-                    frow += WAVE * WI;
-                    load_rows(f);
-                    load_half(hA, pA);
-                    fence_loads();
+                    frow += WI * WAVE;
                 }
-                // columns that reach both half-blocks
+                // --- columns that reach both half-blocks: slots = halves A and B of a column
                 pB += (size_t)n1 * STEP;
-                for (int x = ncol - n1; x > 0; --x) {
-                    settle(hA, f[0]);
-                    load_half(hB, pB);
+                auto load_AB = [&](Batch &b, int col) {
+                    rows(b.fX, col);
+                    load_half(b.X, pA + (size_t)col * STEP);
+                    load_half(b.Y, pB + (size_t)col * STEP);
                     fence_loads();
-                    operands(f);
-                    relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
-                    settle(hB);
-                    frow += WAVE * WI;
-                    load_rows(f);
-                    pA += STEP;
-                    pB += STEP;
-                    load_half(hA, pA);
-                    fence_loads();
-                    relax8<NC, COUNT>(acc, 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
+                };
+                auto compute_AB = [&](Batch &b) {
+                    operands(b.fX);
+                    relax8<NC, COUNT>(acc, 0, b.X.t, b.X.mn, b.X.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 8, b.Y.t, b.Y.mn, b.Y.mx, G, c, n_blocks);
+                };
+                auto settle_AB = [&](const Batch &b) {
+                    settle(b.X, b.fX[0]);
+                    settle(b.Y);
+                };
+                left = ncol - n1;
+                if (left >= 1) {
+                    load_AB(b0, 0);
+                    for (; left >= 2; left -= 2) {
+                        settle_AB(b0);
+                        load_AB(b1, 1);
+                        compute_AB(b0);
+                        settle_AB(b1);
+                        load_AB(b0, 2);
+                        compute_AB(b1);
+                        pA += 2 * STEP;
+                        pB += 2 * STEP;
+                        frow += 2 * WI * WAVE;
+                    }
+                    if (left == 1) {
+                        settle_AB(b0);
+                        compute_AB(b0);
+                    }
                 }
             }
             __syncthreads();                           // every wave is done reading Fprev
@@ -405,7 +442,7 @@ hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S
 size_t fast_table_ints(int K, int S)
 {
     const int KP = 16 * ((K + 15) / 16);
-    return ((size_t)K * S * K + 8) * (size_t)((KP / 8) * HB_INTS);     // 8 records of padding
+    return ((size_t)K * S * K + 32) * (size_t)((KP / 8) * HB_INTS);     // 32 records of padding
 }
 
 constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (plan) run
@@ -413,7 +450,7 @@ constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (p
 template <int NWK, int WI, int NC>
 static size_t fast_lds_bytes()
 {
-    return (size_t)NC * (NWK * 16 + WI) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
+    return (size_t)NC * (NWK * 16 + 6 * WI) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
 }
 
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
