@@ -186,7 +186,7 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
         HIPCHK(hipMalloc(&h->d_sizes, (size_t)S * 4));
         HIPCHK(hipMemcpyAsync(h->d_sizes, sizes.data(), (size_t)S * 4, hipMemcpyHostToDevice,
                               h->stream));
-        HIPCHK(hipMalloc(&h->pb.hist, 256 * 256 * 4));
+        HIPCHK(hipMalloc(&h->pb.hist, (256 * 256 + 256) * 4));   // counts + digit totals
         HIPCHK(hipMalloc(&h->d_ncount, 2 * 4));
         HIPCHK(hipMalloc(&h->d_state, sizeof(SolveState)));
         HIPCHK(hipMemsetAsync(h->d_state, 0, sizeof(SolveState), h->stream));

@@ -110,7 +110,7 @@ __device__ __forceinline__ int64_t wave_prefix_min_i64(int64_t v, int lane)
 
 struct PrepBuffers {
     int32_t *keys[2];        // [cap] each
-    uint32_t *hist;          // [256 * 256]
+    uint32_t *hist;          // [256 * 256] slice counts + [256] digit totals
     uint32_t *block_cnt;     // [cap / 4096 + 2]
     int cap;
 };

@@ -92,14 +92,54 @@ __global__ __launch_bounds__(1024) void scan_u32_kernel(uint32_t *__restrict__ v
     if (total_out && t == 1023) *total_out = part[1023];
 }
 
+// Offsets of one radix pass from the per-slice digit counts hist[digit][slice]: one block per
+// digit scans its SORT_BLOCKS counts in place (exclusive) and leaves the digit's total in
+// totals[digit]; digit_base_kernel then scans the 256 totals.
+__global__ __launch_bounds__(SORT_BLOCKS) void digit_scan_kernel(uint32_t *__restrict__ hist,
+                                                                 uint32_t *__restrict__ totals)
+{
+    __shared__ uint32_t part[SORT_BLOCKS];
+    const int t = threadIdx.x;
+    uint32_t *row = hist + blockIdx.x * SORT_BLOCKS;
+    const uint32_t own = row[t];
+    part[t] = own;
+    __syncthreads();
+    for (int off = 1; off < SORT_BLOCKS; off <<= 1) {
+        const uint32_t o = (t >= off) ? part[t - off] : 0u;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    row[t] = part[t] - own;
+    if (t == SORT_BLOCKS - 1) totals[blockIdx.x] = part[t];
+}
+
+__global__ __launch_bounds__(RADIX) void digit_base_kernel(uint32_t *__restrict__ totals)
+{
+    __shared__ uint32_t part[RADIX];
+    const int t = threadIdx.x;
+    const uint32_t own = totals[t];
+    part[t] = own;
+    __syncthreads();
+    for (int off = 1; off < RADIX; off <<= 1) {
+        const uint32_t o = (t >= off) ? part[t - off] : 0u;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    totals[t] = part[t] - own;
+}
+
 __global__ __launch_bounds__(WAVE) void radix_scatter_kernel(const int32_t *__restrict__ keys_in,
                                                              int32_t *__restrict__ keys_out, int n,
                                                              int shift,
-                                                             const uint32_t *__restrict__ offs)
+                                                             const uint32_t *__restrict__ offs,
+                                                             const uint32_t *__restrict__ digit_base)
 {
     __shared__ uint32_t base[RADIX];
     const int lane = threadIdx.x;
-    for (int x = lane; x < RADIX; x += WAVE) base[x] = offs[x * SORT_BLOCKS + blockIdx.x];
+    for (int x = lane; x < RADIX; x += WAVE)
+        base[x] = digit_base[x] + offs[x * SORT_BLOCKS + blockIdx.x];
     __syncthreads();
     int lo, hi;
     slice_of(n, blockIdx.x, lo, hi);
@@ -247,10 +287,12 @@ hipError_t launch_sort_dedup(hipStream_t st, PrepBuffers &pb, int n, int key_bit
     for (int shift = 0; shift < key_bits; shift += 8) {
         hipLaunchKernelGGL(radix_hist_kernel, dim3(SORT_BLOCKS), dim3(WAVE), 0, st,
                            pb.keys[cur], n, shift, pb.hist);
-        hipLaunchKernelGGL(scan_u32_kernel, dim3(1), dim3(1024), 0, st, pb.hist,
-                           RADIX * SORT_BLOCKS, (uint32_t *)nullptr);
+        uint32_t *totals = pb.hist + RADIX * SORT_BLOCKS;
+        hipLaunchKernelGGL(digit_scan_kernel, dim3(RADIX), dim3(SORT_BLOCKS), 0, st, pb.hist,
+                           totals);
+        hipLaunchKernelGGL(digit_base_kernel, dim3(1), dim3(RADIX), 0, st, totals);
         hipLaunchKernelGGL(radix_scatter_kernel, dim3(SORT_BLOCKS), dim3(WAVE), 0, st,
-                           pb.keys[cur], pb.keys[cur ^ 1], n, shift, pb.hist);
+                           pb.keys[cur], pb.keys[cur ^ 1], n, shift, pb.hist, totals);
         cur ^= 1;
     }
     const int nb = (n + DEDUP_TILE - 1) / DEDUP_TILE;
