@@ -320,7 +320,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             const int grid = std::max(1, std::min((bound + nc - 1) / nc, h->fast_grid_max[nc]));
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
-                        /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr};
+                        /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr, nullptr};
             HIPCHK(launch_recurrence_fast(st, fa, (flags & ALPA_DP_COUNT_WORK) ? FAST_MODE_COUNT
                                                                               : FAST_MODE_BATCH,
                                           nc, grid));
@@ -341,7 +341,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
         FastArgs fa{p, h->d_recs, h->d_sizes, &h->d_state->best_c,
                     &h->d_state->plan_n, &h->d_state->plan_ticket, &h->d_state->wave_relax,
-                    nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall};
+                    nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall, &h->d_state->best_s};
         HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1, 1));
     } else {
         HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, &h->d_state->best_c,

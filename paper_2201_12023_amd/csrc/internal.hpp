@@ -145,6 +145,7 @@ struct FastArgs {
     int32_t *Fmin, *Sbest;
     int dummy_idx;           // spare slot of Fmin / Sbest for the waves that own no result
     int32_t *F_all;          // [Smax+1][(K+2)*(D+1)], plan mode only
+    const int32_t *s_top_p;  // plan mode only: number of stages of the winner (device memory)
 };
 enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);

@@ -150,7 +150,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
     unsigned long long *wave_relax, int64_t *chunk_min, int prune, int descending,
     int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest, int dummy_idx,
-    int32_t *__restrict__ F_all)
+    int32_t *__restrict__ F_all, const int32_t *__restrict__ s_top_p)
 {
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     constexpr int NT = WAVE * NWK * WI;
@@ -211,8 +211,12 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 continue;
             }
         }
+        // Plan recovery walks back from F(s*, first layer 1, all devices): only layers up to
+        // s* are needed, and of layer s only first layers (0-based) >= s* - s, since each of
+        // the s* - s stages in front takes at least one layer.
+        const int s_top = DUMP ? min(p.Smax, __builtin_amdgcn_readfirstlane(*s_top_p)) : p.Smax;
         if (DUMP) {
-            const int total = (p.Smax + 1) * LS;
+            const int total = (s_top + 1) * LS;
             for (int x = tid; x < total; x += NT) F_all[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
             __syncthreads();
         }
@@ -220,7 +224,11 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
 #pragma unroll
         for (int e = 0; e < NC; ++e) { best[e] = DEV_INF; sbest[e] = 0; }
         unsigned n_blocks = 0;
-        for (int s = 1; s <= p.Smax; ++s) {
+        for (int s = 1; s <= s_top; ++s) {
+            const bool needA = !DUMP || rowA + 7 >= s_top - s;
+            const bool needB = !DUMP || rowB + 7 >= s_top - s;
+            auto mnA = [&](const HalfColumn &h) { return needA ? h.mn : DEV_INF; };   // "no entry
+            auto mnB = [&](const HalfColumn &h) { return needB ? h.mn : DEV_INF; };   //  passes"
             int32_t acc[NC][16];                       // [0..7] half-block A, [8..15] half-block B
 #pragma unroll
             for (int e = 0; e < NC; ++e)
@@ -250,8 +258,8 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                     for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, i += WI) {
                         load_half(hA, pA);
                         load_half(hB, pB);
-                        relax8<NC, COUNT>(acc, 0, hA.t, hA.mn, hA.mx, G, c, n_blocks);
-                        if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, hB.mn, hB.mx, G, c, n_blocks);
+                        relax8<NC, COUNT>(acc, 0, hA.t, mnA(hA), hA.mx, G, c, n_blocks);
+                        if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, mnB(hB), hB.mx, G, c, n_blocks);
                     }
                     continue;
                 }
@@ -286,12 +294,17 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 };
                 auto compute_AA = [&](Batch &b) {
                     operands(b.fX);
-                    relax8<NC, COUNT>(acc, 0, b.X.t, b.X.mn, b.X.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 0, b.X.t, mnA(b.X), b.X.mx, G, c, n_blocks);
                     operands(b.fY);
-                    relax8<NC, COUNT>(acc, 0, b.Y.t, b.Y.mn, b.Y.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 0, b.Y.t, mnA(b.Y), b.Y.mx, G, c, n_blocks);
                 };
                 const int n1 = max(0, min((rowB - i0 + WI - 1) / WI, ncol));
                 int left = n1;
+                if (DUMP && !needA) {                  // nothing to do in this phase
+                    left = 0;
+                    pA += (size_t)n1 * STEP;
+                    frow += n1 * WI * WAVE;
+                }
                 if (left >= 2) {
                     load_AA(b0, 0);
                     for (; left >= 4; left -= 4) {
@@ -316,7 +329,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                     rows(b0.fX, 0);
                     load_half(b0.X, pA);
                     operands(b0.fX);
-                    relax8<NC, COUNT>(acc, 0, b0.X.t, b0.X.mn, b0.X.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 0, b0.X.t, mnA(b0.X), b0.X.mx, G, c, n_blocks);
                     pA += STEP;
                     frow += WI * WAVE;
                 }
@@ -330,8 +343,8 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                 };
                 auto compute_AB = [&](Batch &b) {
                     operands(b.fX);
-                    relax8<NC, COUNT>(acc, 0, b.X.t, b.X.mn, b.X.mx, G, c, n_blocks);
-                    relax8<NC, COUNT>(acc, 8, b.Y.t, b.Y.mn, b.Y.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 0, b.X.t, mnA(b.X), b.X.mx, G, c, n_blocks);
+                    relax8<NC, COUNT>(acc, 8, b.Y.t, mnB(b.Y), b.Y.mx, G, c, n_blocks);
                 };
                 auto settle_AB = [&](const Batch &b) {
                     settle(b.X, b.fX[0]);
@@ -460,7 +473,7 @@ static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
     hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>), dim3(grid),
                        dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
                        a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
-                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all);
+                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p);
     return hipGetLastError();
 }
 
