@@ -95,6 +95,38 @@ int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table,
                    int K, int N, int M, int B,
                    const alpa_shape_t *shapes, int num_shapes);
 
+/*
+ * Same handle, with the t_intra table built on the device from profiled options
+ * (Sec. 5.2, the paragraph that defines t_intra, Eq. 5, and the intra-op loop nest of
+ * Alg. 1): for stage (k..i), submesh shape q and s stages from this one to the last,
+ *   t_intra = min over options o with mem_stage + s * mem_act <= mem_device of t_l,
+ * +infinity (ALPA_DP_INF_I32) if no option fits; s = 1..K.
+ *
+ *   t_l        HOST int32 [k][i][q][o] (C order, extents K x K x num_shapes x
+ *              num_options), microseconds; ALPA_DP_INF_I32 = the option does not exist.
+ *              An option is a logical mesh shape with n_q * m_q devices combined with
+ *              an intra-op option.  Entries with i < k are ignored.
+ *   mem_stage  HOST int64, same layout: bytes per device to run the stage.
+ *   mem_act    HOST int64, same layout: bytes per device per stored set of activations.
+ *   mem_device bytes per device.
+ *   The other arguments are those of alpa_dp_create.  All arrays are read during the
+ *   call only.
+ *
+ * Errors: those of alpa_dp_create, and EINVAL for num_options < 1 or >
+ * ALPA_DP_MAX_OPTIONS, a negative latency, a memory figure outside [0, 2^52), or
+ * mem_device outside [0, 2^62).
+ */
+#define ALPA_DP_MAX_OPTIONS 32
+int alpa_dp_create_from_profiles(alpa_dp_t **out, const int32_t *t_l,
+                                 const int64_t *mem_stage, const int64_t *mem_act,
+                                 int num_options, int64_t mem_device,
+                                 int K, int N, int M, int B,
+                                 const alpa_shape_t *shapes, int num_shapes);
+
+/* Copies the handle's table, C order [s-1][k][i][q] (K x K x K x num_shapes int32), to
+ * the HOST array out_table.  Blocking. */
+int alpa_dp_get_table(alpa_dp_t *h, int32_t *out_table);
+
 /* Queue all later work of this handle on `hip_stream` (a hipStream_t; e.g. the
  * cuda_stream field of a torch.cuda.Stream).  The caller keeps the stream alive. */
 int alpa_dp_set_stream(alpa_dp_t *h, void *hip_stream);
@@ -141,6 +173,30 @@ int alpa_dp_solve(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
  */
 int alpa_dp_solve_dev(alpa_dp_t *h, const int32_t *d_tmax, int n_tmax, unsigned flags,
                       int64_t *d_out_T, alpa_plan_t *d_out_plan);
+
+/*
+ * Sweep over the number of microbatches (Sec. 5.2: B is a hyper-parameter found by
+ * enumeration).  F of Eq. 3 does not depend on B, so the recurrence runs once for the
+ * candidate list and Eq. 4 plus the selection run once per B value.
+ *
+ *   tmax, n_tmax  as for alpa_dp_solve (HOST pointer or NULL).
+ *   flags     ALPA_DP_GENERIC as for alpa_dp_solve.  ALPA_DP_PRUNE: every candidate is
+ *             still evaluated (the early exit of Alg. 1 depends on B); the rule is applied
+ *             per B value afterwards, so that out_plans[b].n_evaluated and every other
+ *             field equal those of alpa_dp_solve with B = B_values[b] and the same flags.
+ *   B_values  HOST array of n_B values, each >= 1, 1 <= n_B <= ALPA_DP_MAX_SWEEP.
+ *   out_plans HOST array of n_B plans, caller-owned; out_plans[b] is the best plan for
+ *             B_values[b] (num_stages == 0 and T_star == ALPA_DP_INF_I64 if infeasible).
+ *
+ * The handle's own B and the running best of alpa_dp_best() are not touched.  Blocking.
+ * On the first call (and when n_B grows) device memory for n_B sets of layers is
+ * allocated: n_B * (min(K, N*M) + 1) * (K + 2) * (N*M + 1) * 4 bytes when K <= 64 and
+ * N*M <= 64.  Errors: EINVAL (null pointers, n_B or a B value out of range, and the
+ * candidate-list errors of alpa_dp_solve), ENOMEM, EHIP.
+ */
+#define ALPA_DP_MAX_SWEEP 256
+int alpa_dp_solve_sweep(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
+                        const int32_t *B_values, int n_B, alpa_plan_t *out_plans);
 
 /* Ascending distinct candidate list of the last solve on this handle: copies at most
  * `cap` values to the HOST array `out` and stores the count in *out_n.  Blocking. */

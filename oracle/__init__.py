@@ -1,4 +1,4 @@
-"""ctypes wrapper around the CPU oracle (``alpa_dp_oracle.c``).
+"""ctypes wrapper around the CPU oracle (``alpa_dp_oracle.c``, ``alpa_table_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, the smoke check and the
 benchmark's ``cpu_baseline`` leg.  It never imports the HIP package and the HIP
@@ -21,6 +21,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "alpa_dp_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+_SRC_TABLE = os.path.join(_HERE, "alpa_table_oracle.c")
+_LIB_TABLE = os.path.join(_HERE, "libtable_oracle.so")
 
 INF64 = np.iinfo(np.int64).max
 INF32 = np.iinfo(np.int32).max
@@ -29,9 +31,10 @@ MAX_K = 256
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, -O2, no threads)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall",
-                               "-o", _LIB, _SRC])
+    for src, out in ((_SRC, _LIB), (_SRC_TABLE, _LIB_TABLE)):
+        if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
+            subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall",
+                                   "-o", out, src])
     return _LIB
 
 
@@ -70,6 +73,32 @@ def lib():
         assert L.orc_max_k() == MAX_K
         _lib = L
     return _lib
+
+
+_lib_table = None
+
+
+def lib_table():
+    global _lib_table
+    if _lib_table is None:
+        build()
+        _lib_table = ctypes.CDLL(_LIB_TABLE)
+    return _lib_table
+
+
+def build_table(t_l, mem_stage, mem_act, mem_device: int) -> np.ndarray:
+    """t_intra[s-1][k][i][q] from profiled options [k][i][q][o] (Sec. 5.2, Eq. 5, Alg. 1)."""
+    t_l = np.ascontiguousarray(t_l, dtype=np.int32)
+    mem_stage = np.ascontiguousarray(mem_stage, dtype=np.int64)
+    mem_act = np.ascontiguousarray(mem_act, dtype=np.int64)
+    K, K2, S, O = t_l.shape
+    assert K == K2 and mem_stage.shape == t_l.shape and mem_act.shape == t_l.shape
+    table = np.empty((K, K, K, S), dtype=np.int32)
+    rc = lib_table().orc_build_table(_i32p(t_l), _i64p(mem_stage), _i64p(mem_act), K, S, O,
+                                     ctypes.c_int64(int(mem_device)), _i32p(table))
+    if rc != 0:
+        raise RuntimeError(f"orc_build_table failed: {rc}")
+    return table
 
 
 def _i32p(a):

@@ -16,14 +16,17 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libalpa_dp.so")
 
 MAX_K = 256
+MAX_SWEEP = 256
+MAX_OPTIONS = 32
 INF_I32 = 2**31 - 1
 INF_I64 = 2**63 - 1
 ALPA_DP_PRUNE = 1
 ALPA_DP_GENERIC = 2
 ALPA_DP_COUNT_WORK = 4
 
-SYMBOLS = ["alpa_dp_create", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_count_candidates",
-           "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_candidates", "alpa_dp_best",
+SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_count_candidates",
+           "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
+           "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
            "alpa_dp_last_error"]
 
@@ -71,11 +74,17 @@ def load():
     vp, i32p, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
     L.alpa_dp_create.argtypes = [ctypes.POINTER(vp), vp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                  ctypes.c_int, ctypes.POINTER(alpa_shape_t), ctypes.c_int]
+    L.alpa_dp_create_from_profiles.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ctypes.c_int,
+                                               ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_int, ctypes.c_int,
+                                               ctypes.POINTER(alpa_shape_t), ctypes.c_int]
+    L.alpa_dp_get_table.argtypes = [vp, vp]
     L.alpa_dp_set_stream.argtypes = [vp, vp]
     L.alpa_dp_set_B.argtypes = [vp, ctypes.c_int]
     L.alpa_dp_count_candidates.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]
     L.alpa_dp_solve.argtypes = [vp, vp, ctypes.c_int, ctypes.c_uint, vp, vp]
     L.alpa_dp_solve_dev.argtypes = [vp, vp, ctypes.c_int, ctypes.c_uint, vp, vp]
+    L.alpa_dp_solve_sweep.argtypes = [vp, vp, ctypes.c_int, ctypes.c_uint, vp, ctypes.c_int, vp]
     L.alpa_dp_candidates.argtypes = [vp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
     L.alpa_dp_best.argtypes = [vp, ctypes.POINTER(alpa_plan_t)]
     L.alpa_dp_last_timing.argtypes = [vp] + [ctypes.POINTER(ctypes.c_float)] * 3
@@ -104,6 +113,31 @@ def alpa_dp_create(cost_table, K, N, M, B, shapes):
     h = ctypes.c_void_p()
     _check(L.alpa_dp_create(ctypes.byref(h), table.ctypes.data, K, N, M, B, arr, S))
     return h
+
+
+def alpa_dp_create_from_profiles(t_l, mem_stage, mem_act, mem_device, K, N, M, B, shapes):
+    """t_l int32 / mem_stage, mem_act int64 numpy arrays [K, K, S, O] (host); the table is built
+    on the device."""
+    L = load()
+    shp = np.ascontiguousarray(shapes, dtype=np.int32).reshape(-1, 2)
+    S = shp.shape[0]
+    t = np.ascontiguousarray(t_l, dtype=np.int32)
+    ms = np.ascontiguousarray(mem_stage, dtype=np.int64)
+    ma = np.ascontiguousarray(mem_act, dtype=np.int64)
+    if t.size % (K * K * S) != 0 or ms.size != t.size or ma.size != t.size:
+        raise ValueError("profile arrays must have K*K*num_shapes*num_options entries each")
+    O = t.size // (K * K * S)
+    arr = (alpa_shape_t * S)(*[alpa_shape_t(int(n), int(m)) for n, m in shp])
+    h = ctypes.c_void_p()
+    _check(L.alpa_dp_create_from_profiles(ctypes.byref(h), t.ctypes.data, ms.ctypes.data,
+                                          ma.ctypes.data, O, int(mem_device), K, N, M, B, arr, S))
+    return h
+
+
+def alpa_dp_get_table(h, K, S) -> np.ndarray:
+    out = np.empty((K, K, K, S), dtype=np.int32)
+    _check(load().alpa_dp_get_table(h, out.ctypes.data))
+    return out
 
 
 def alpa_dp_set_stream(h, stream):
@@ -149,6 +183,23 @@ def alpa_dp_solve_dev(h, d_tmax, n_tmax, flags, d_out_T, d_out_plan):
         return None if t is None else ctypes.c_void_p(int(t.data_ptr()))
     _check(load().alpa_dp_solve_dev(h, ptr(d_tmax), int(n_tmax), int(flags), ptr(d_out_T),
                                     ptr(d_out_plan)))
+
+
+def alpa_dp_solve_sweep(h, tmax, B_values, n_tmax=None, flags=0):
+    """One plan dict per value of B_values (int32 array-like, host); tmax as for alpa_dp_solve."""
+    L = load()
+    if tmax is not None:
+        t = np.ascontiguousarray(tmax, dtype=np.int32)
+        n = int(t.size) if n_tmax is None else int(n_tmax)
+        tp = t.ctypes.data
+    else:
+        n = 0 if n_tmax is None else int(n_tmax)
+        tp = None
+    B = np.ascontiguousarray(B_values, dtype=np.int32)
+    plans = (alpa_plan_t * max(int(B.size), 1))()
+    _check(L.alpa_dp_solve_sweep(h, tp, n, flags, B.ctypes.data if B.size else None, int(B.size),
+                                 ctypes.addressof(plans)))
+    return [plans[b].as_dict() for b in range(int(B.size))]
 
 
 def alpa_dp_candidates(h) -> np.ndarray:

@@ -55,6 +55,13 @@ struct alpa_dp {
     SolveState *d_state = nullptr;
     int32_t *d_scratch = nullptr, *d_Fall = nullptr, *d_tmpFS = nullptr;
     alpa_plan_t *d_plan_tmp = nullptr, *d_best_plan = nullptr;
+    // sweep over B (allocated on first use, for up to sw_cap values)
+    int sw_cap = 0;
+    int32_t *d_sw_B = nullptr, *d_sw_c = nullptr, *d_sw_s = nullptr, *d_sw_FS = nullptr;
+    int32_t *d_sw_n = nullptr;      // [2]: number of B values, ticket of the plan-recovery run
+    SolveState *d_sw_state = nullptr;
+    int32_t *d_sw_Fall = nullptr;
+    alpa_plan_t *d_sw_plans = nullptr;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     bool any_solve = false, timed = false;
     int last_host_n = 0;
@@ -94,6 +101,36 @@ static int alloc_candidate_arrays(alpa_dp *h, int cap)
     return ALPA_DP_OK;
 }
 
+static void free_sweep_arrays(alpa_dp *h)
+{
+    (void)hipFree(h->d_sw_B); (void)hipFree(h->d_sw_c); (void)hipFree(h->d_sw_s);
+    (void)hipFree(h->d_sw_FS); (void)hipFree(h->d_sw_n); (void)hipFree(h->d_sw_state);
+    (void)hipFree(h->d_sw_Fall); (void)hipFree(h->d_sw_plans);
+    h->d_sw_B = h->d_sw_c = h->d_sw_s = h->d_sw_FS = h->d_sw_n = h->d_sw_Fall = nullptr;
+    h->d_sw_state = nullptr;
+    h->d_sw_plans = nullptr;
+    h->sw_cap = 0;
+}
+
+static int alloc_sweep_arrays(alpa_dp *h, int n_B)
+{
+    free_sweep_arrays(h);
+    const size_t n = (size_t)n_B;
+    HIPCHK(hipMalloc(&h->d_sw_B, n * 4));
+    HIPCHK(hipMalloc(&h->d_sw_c, n * 4));
+    HIPCHK(hipMalloc(&h->d_sw_s, n * 4));
+    HIPCHK(hipMalloc(&h->d_sw_FS, 2 * (n + 1) * 4));
+    HIPCHK(hipMalloc(&h->d_sw_n, 2 * 4));
+    HIPCHK(hipMalloc(&h->d_sw_state, n * sizeof(SolveState)));
+    HIPCHK(hipMalloc(&h->d_sw_plans, n * sizeof(alpa_plan_t)));
+    if (h->fast_ok) {          // one slab of layers per B value; the general kernel reuses d_Fall
+        const size_t slab = (size_t)(h->p.Smax + 1) * (size_t)(h->p.K + 2) * (h->p.D + 1);
+        HIPCHK(hipMalloc(&h->d_sw_Fall, n * slab * 4));
+    }
+    h->sw_cap = n_B;
+    return ALPA_DP_OK;
+}
+
 static int bits_for(uint32_t v)
 {
     int b = 1;
@@ -122,6 +159,7 @@ extern "C" void alpa_dp_destroy(alpa_dp_t *h)
     (void)hipSetDevice(h->device);
     (void)hipStreamSynchronize(h->stream);
     free_candidate_arrays(h);
+    free_sweep_arrays(h);
     (void)hipFree(h->d_table); (void)hipFree(h->d_sizes); (void)hipFree(h->d_recs);
     (void)hipFree(h->pb.hist); (void)hipFree(h->d_ncount); (void)hipFree(h->d_state); (void)hipFree(h->d_scratch);
     (void)hipFree(h->d_Fall); (void)hipFree(h->d_tmpFS); (void)hipFree(h->d_plan_tmp); (void)hipFree(h->d_best_plan);
@@ -130,12 +168,11 @@ extern "C" void alpa_dp_destroy(alpa_dp_t *h)
     delete h;
 }
 
-extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K, int N, int M,
-                              int B, const alpa_shape_t *shapes, int num_shapes)
+// Argument checks common to both ways of creating a handle; fills sizes[q] = n_q * m_q.
+static int check_problem(int K, int N, int M, int B, const alpa_shape_t *shapes, int num_shapes,
+                         std::vector<int32_t> &sizes)
 {
-    if (!out) return fail(ALPA_DP_EINVAL, "out is null");
-    *out = nullptr;
-    if (!cost_table || !shapes) return fail(ALPA_DP_EINVAL, "cost_table or shapes is null");
+    if (!shapes) return fail(ALPA_DP_EINVAL, "shapes is null");
     if (K < 1 || K > ALPA_DP_MAX_K) return fail(ALPA_DP_EINVAL, "K out of range");
     if (N < 1 || M < 1 || (long long)N * M > ALPA_DP_MAX_DEVICES)
         return fail(ALPA_DP_EINVAL, "N x M out of range");
@@ -143,7 +180,7 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
     if (B < 1) return fail(ALPA_DP_EINVAL, "B must be >= 1");
     if (num_shapes < 1 || num_shapes > ALPA_DP_MAX_SHAPES)
         return fail(ALPA_DP_EINVAL, "num_shapes out of range");
-    std::vector<int32_t> sizes(num_shapes);
+    sizes.resize(num_shapes);
     for (int q = 0; q < num_shapes; ++q) {
         const int n = shapes[q].n, m = shapes[q].m;
         const bool one_d = n == 1 && m >= 1 && m <= M && (m & (m - 1)) == 0;
@@ -151,7 +188,107 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
         if (!one_d && !two_d) return fail(ALPA_DP_EINVAL, "shape outside the submesh family");
         sizes[q] = n * m;
     }
-    const int S = num_shapes, D = N * M;
+    return ALPA_DP_OK;
+}
+
+// Device side of handle creation.  `fill_table` puts the table into h->d_table (already
+// allocated) and sets h->max_finite; everything else follows from those two.
+template <class FillTable>
+static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillTable fill_table)
+{
+    const int K = h->p.K, S = h->p.S, D = h->p.D;
+    HIPCHK(hipGetDevice(&h->device));
+    hipDeviceProp_t prop;
+    HIPCHK(hipGetDeviceProperties(&prop, h->device));
+    h->n_cu = prop.multiProcessorCount;
+    for (auto &e : h->ev) HIPCHK(hipEventCreate(&e));
+    const size_t tbytes = (size_t)K * K * K * S * 4;
+    HIPCHK(hipMalloc(&h->d_table, tbytes));
+    {
+        int rc = fill_table();
+        if (rc) return rc;
+    }
+    if (h->max_finite >= 0 && (long long)K * h->max_finite >= (1ll << 30))
+        return fail(ALPA_DP_EOVERFLOW, "K * largest finite latency >= 2^30");
+    h->key_bits_table = bits_for((uint32_t)(h->max_finite + 1));
+    h->n_table_keys = K * (K * (K + 1) / 2) * S;
+    HIPCHK(hipMalloc(&h->d_sizes, (size_t)S * 4));
+    HIPCHK(hipMemcpyAsync(h->d_sizes, sizes.data(), (size_t)S * 4, hipMemcpyHostToDevice,
+                          h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));      // `sizes` may go away after the return
+    HIPCHK(hipMalloc(&h->pb.hist, (256 * 256 + 256) * 4));   // counts + digit totals
+    HIPCHK(hipMalloc(&h->d_ncount, 2 * 4));
+    HIPCHK(hipMalloc(&h->d_state, sizeof(SolveState)));
+    HIPCHK(hipMemsetAsync(h->d_state, 0, sizeof(SolveState), h->stream));
+    HIPCHK(hipMalloc(&h->d_tmpFS, 4 * 4));
+    HIPCHK(hipMalloc(&h->d_plan_tmp, sizeof(alpa_plan_t)));
+    HIPCHK(hipMalloc(&h->d_best_plan, sizeof(alpa_plan_t)));
+    HIPCHK(launch_init_best_plan(h->stream, h->d_best_plan));
+    const size_t LS = (size_t)(K + 2) * (D + 1);
+    HIPCHK(hipMalloc(&h->d_Fall, (size_t)(h->p.Smax + 1) * LS * 4));
+    // general kernel: two F layers per resident workgroup, at most 256 MiB in total
+    int gg = h->n_cu * 4;
+    while (gg > 1 && (size_t)gg * 2 * LS * 4 > (256ull << 20)) gg /= 2;
+    h->generic_grid_max = gg;
+    HIPCHK(hipMalloc(&h->d_scratch, (size_t)gg * 2 * LS * 4));
+    // register/LDS kernel
+    h->fast_ok = K <= 64 && D <= 64;
+    if (h->fast_ok) {
+        h->KP = 16 * ((K + 15) / 16);
+        HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
+        HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
+        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
+        for (int nc = 1; nc <= 2; ++nc) {
+            int per_cu = fast_kernel_blocks_per_cu(K, nc);
+            if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
+            if (const char *e = getenv("ALPA_DP_WG_PER_CU")) {   // tuning aid
+                const int v = atoi(e);
+                if (v >= 1 && v < per_cu) per_cu = v;
+            }
+            h->fast_grid_max[nc] = h->n_cu * per_cu;
+        }
+    }
+    int rc2 = alloc_candidate_arrays(h, std::max(h->n_table_keys, 1024));
+    if (rc2) return rc2;
+    // length of the full candidate list
+    rc2 = queue_table_candidates(h);
+    if (rc2) return rc2;
+    uint32_t nd = 0;
+    HIPCHK(hipMemcpyAsync(&nd, h->d_ncount, 4, hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    h->n_distinct = (int)nd;
+    return ALPA_DP_OK;
+}
+
+template <class FillTable>
+static int create_handle(alpa_dp_t **out, int K, int N, int M, int B,
+                         const std::vector<int32_t> &sizes, FillTable fill_table_for)
+{
+    alpa_dp *h = new (std::nothrow) alpa_dp();
+    if (!h) return fail(ALPA_DP_ENOMEM, "host allocation failed");
+    const int D = N * M;
+    h->p = Problem{K, N, M, D, (int)sizes.size(), std::min(K, D), B};
+    const int rc = create_on_device(h, sizes, [&]() { return fill_table_for(h); });
+    if (rc != ALPA_DP_OK) {
+        std::string keep = g_err;
+        alpa_dp_destroy(h);
+        g_err = keep;
+        return rc;
+    }
+    *out = h;
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K, int N, int M,
+                              int B, const alpa_shape_t *shapes, int num_shapes)
+{
+    if (!out) return fail(ALPA_DP_EINVAL, "out is null");
+    *out = nullptr;
+    if (!cost_table || !shapes) return fail(ALPA_DP_EINVAL, "cost_table or shapes is null");
+    std::vector<int32_t> sizes;
+    int rc = check_problem(K, N, M, B, shapes, num_shapes, sizes);
+    if (rc) return rc;
+    const int S = num_shapes;
     // range check of the part of the table that is used
     int32_t max_finite = -1;
     for (int s = 0; s < K; ++s)
@@ -166,77 +303,79 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
         }
     if (max_finite >= 0 && (long long)K * max_finite >= (1ll << 30))
         return fail(ALPA_DP_EOVERFLOW, "K * largest finite latency >= 2^30");
+    return create_handle(out, K, N, M, B, sizes, [&](alpa_dp *h) -> int {
+        h->max_finite = max_finite;
+        HIPCHK(hipMemcpyAsync(h->d_table, cost_table, (size_t)K * K * K * S * 4,
+                              hipMemcpyHostToDevice, h->stream));
+        return ALPA_DP_OK;
+    });
+}
 
-    alpa_dp *h = new (std::nothrow) alpa_dp();
-    if (!h) return fail(ALPA_DP_ENOMEM, "host allocation failed");
-    h->p = Problem{K, N, M, D, S, std::min(K, D), B};
-    h->max_finite = max_finite;
-    h->key_bits_table = bits_for((uint32_t)(max_finite + 1));
-    h->n_table_keys = K * (K * (K + 1) / 2) * S;
-    int rc = ALPA_DP_OK;
-    auto body = [&]() -> int {
-        HIPCHK(hipGetDevice(&h->device));
-        hipDeviceProp_t prop;
-        HIPCHK(hipGetDeviceProperties(&prop, h->device));
-        h->n_cu = prop.multiProcessorCount;
-        for (auto &e : h->ev) HIPCHK(hipEventCreate(&e));
-        const size_t tbytes = (size_t)K * K * K * S * 4;
-        HIPCHK(hipMalloc(&h->d_table, tbytes));
-        HIPCHK(hipMemcpyAsync(h->d_table, cost_table, tbytes, hipMemcpyHostToDevice, h->stream));
-        HIPCHK(hipMalloc(&h->d_sizes, (size_t)S * 4));
-        HIPCHK(hipMemcpyAsync(h->d_sizes, sizes.data(), (size_t)S * 4, hipMemcpyHostToDevice,
-                              h->stream));
-        HIPCHK(hipMalloc(&h->pb.hist, (256 * 256 + 256) * 4));   // counts + digit totals
-        HIPCHK(hipMalloc(&h->d_ncount, 2 * 4));
-        HIPCHK(hipMalloc(&h->d_state, sizeof(SolveState)));
-        HIPCHK(hipMemsetAsync(h->d_state, 0, sizeof(SolveState), h->stream));
-        HIPCHK(hipMalloc(&h->d_tmpFS, 4 * 4));
-        HIPCHK(hipMalloc(&h->d_plan_tmp, sizeof(alpa_plan_t)));
-        HIPCHK(hipMalloc(&h->d_best_plan, sizeof(alpa_plan_t)));
-        HIPCHK(launch_init_best_plan(h->stream, h->d_best_plan));
-        const size_t LS = (size_t)(K + 2) * (D + 1);
-        HIPCHK(hipMalloc(&h->d_Fall, (size_t)(h->p.Smax + 1) * LS * 4));
-        // general kernel: two F layers per resident workgroup, at most 256 MiB in total
-        int gg = h->n_cu * 4;
-        while (gg > 1 && (size_t)gg * 2 * LS * 4 > (256ull << 20)) gg /= 2;
-        h->generic_grid_max = gg;
-        HIPCHK(hipMalloc(&h->d_scratch, (size_t)gg * 2 * LS * 4));
-        // register/LDS kernel
-        h->fast_ok = K <= 64 && D <= 64;
-        if (h->fast_ok) {
-            h->KP = 16 * ((K + 15) / 16);
-            HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
-            HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
-            HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
-            for (int nc = 1; nc <= 2; ++nc) {
-                int per_cu = fast_kernel_blocks_per_cu(K, nc);
-                if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
-                if (const char *e = getenv("ALPA_DP_WG_PER_CU")) {   // tuning aid
-                    const int v = atoi(e);
-                    if (v >= 1 && v < per_cu) per_cu = v;
-                }
-                h->fast_grid_max[nc] = h->n_cu * per_cu;
+extern "C" int alpa_dp_create_from_profiles(alpa_dp_t **out, const int32_t *t_l,
+                                            const int64_t *mem_stage, const int64_t *mem_act,
+                                            int num_options, int64_t mem_device, int K, int N,
+                                            int M, int B, const alpa_shape_t *shapes,
+                                            int num_shapes)
+{
+    if (!out) return fail(ALPA_DP_EINVAL, "out is null");
+    *out = nullptr;
+    if (!t_l || !mem_stage || !mem_act) return fail(ALPA_DP_EINVAL, "a profile array is null");
+    if (num_options < 1 || num_options > ALPA_DP_MAX_OPTIONS)
+        return fail(ALPA_DP_EINVAL, "num_options out of range");
+    if (mem_device < 0) return fail(ALPA_DP_EINVAL, "mem_device is negative");
+    std::vector<int32_t> sizes;
+    int rc = check_problem(K, N, M, B, shapes, num_shapes, sizes);
+    if (rc) return rc;
+    const int S = num_shapes, O = num_options;
+    // s * mem_act stays far inside int64 when every figure is below 2^52 (s <= 256)
+    for (int k = 0; k < K; ++k)
+        for (int i = k; i < K; ++i) {
+            const size_t e0 = ((size_t)k * K + i) * S * O, cnt = (size_t)S * O;
+            for (size_t x = e0; x < e0 + cnt; ++x) {
+                if (t_l[x] < 0) return fail(ALPA_DP_EINVAL, "negative latency in t_l");
+                if (mem_stage[x] < 0 || mem_act[x] < 0 || mem_stage[x] >= (1ll << 52) ||
+                    mem_act[x] >= (1ll << 52))
+                    return fail(ALPA_DP_EINVAL, "memory figure outside [0, 2^52)");
             }
         }
-        int rc2 = alloc_candidate_arrays(h, std::max(h->n_table_keys, 1024));
-        if (rc2) return rc2;
-        // length of the full candidate list
-        rc2 = queue_table_candidates(h);
-        if (rc2) return rc2;
-        uint32_t nd = 0;
-        HIPCHK(hipMemcpyAsync(&nd, h->d_ncount, 4, hipMemcpyDeviceToHost, h->stream));
-        HIPCHK(hipStreamSynchronize(h->stream));
-        h->n_distinct = (int)nd;
-        return ALPA_DP_OK;
-    };
-    rc = body();
-    if (rc != ALPA_DP_OK) {
-        std::string keep = g_err;
-        alpa_dp_destroy(h);
-        g_err = keep;
-        return rc;
-    }
-    *out = h;
+    if (mem_device >= (1ll << 62)) return fail(ALPA_DP_EINVAL, "mem_device too large");
+    return create_handle(out, K, N, M, B, sizes, [&](alpa_dp *h) -> int {
+        const size_t n = (size_t)K * K * S * O;
+        int32_t *d_t = nullptr, *d_max = nullptr;
+        int64_t *d_ms = nullptr, *d_ma = nullptr;
+        auto body = [&]() -> int {
+            HIPCHK(hipMalloc(&d_t, n * 4));
+            HIPCHK(hipMalloc(&d_ms, n * 8));
+            HIPCHK(hipMalloc(&d_ma, n * 8));
+            HIPCHK(hipMalloc(&d_max, 4));
+            HIPCHK(hipMemcpyAsync(d_t, t_l, n * 4, hipMemcpyHostToDevice, h->stream));
+            HIPCHK(hipMemcpyAsync(d_ms, mem_stage, n * 8, hipMemcpyHostToDevice, h->stream));
+            HIPCHK(hipMemcpyAsync(d_ma, mem_act, n * 8, hipMemcpyHostToDevice, h->stream));
+            HIPCHK(launch_build_table(h->stream, d_t, d_ms, d_ma, K, S, O, mem_device, h->d_table,
+                                      d_max));
+            int32_t mx = -1;
+            HIPCHK(hipMemcpyAsync(&mx, d_max, 4, hipMemcpyDeviceToHost, h->stream));
+            HIPCHK(hipStreamSynchronize(h->stream));
+            h->max_finite = mx;
+            return ALPA_DP_OK;
+        };
+        const int rc2 = body();
+        (void)hipFree(d_t); (void)hipFree(d_ms); (void)hipFree(d_ma); (void)hipFree(d_max);
+        return rc2;
+    });
+}
+
+extern "C" int alpa_dp_get_table(alpa_dp_t *h, int32_t *out_table)
+{
+    if (!h || !out_table) return fail(ALPA_DP_EINVAL, "null argument");
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    const size_t bytes = (size_t)h->p.K * h->p.K * h->p.K * h->p.S * 4;
+    HIPCHK(hipMemcpyAsync(out_table, h->d_table, bytes, hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
     return ALPA_DP_OK;
 }
 
@@ -271,8 +410,10 @@ static int candidate_bound(const alpa_dp *h, bool have_list, int n_tmax)
     return std::min(h->n_distinct, n_tmax);
 }
 
+// n_B > 0: sweep over the B values in d_sw_B (Eq. 4 and the selection once per value, plans
+// to d_sw_plans); otherwise one solve with the handle's B.
 static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigned flags,
-                          int64_t *d_out_T, alpa_plan_t *d_out_plan, int key_bits)
+                          int64_t *d_out_T, alpa_plan_t *d_out_plan, int key_bits, int n_B = 0)
 {
     const Problem &p = h->p;
     const bool have_list = d_tmax != nullptr;
@@ -290,7 +431,10 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         if (rc) return rc;
     }
     const int bound = candidate_bound(h, have_list, n_tmax);
-    const int prune = (flags & ALPA_DP_PRUNE) ? 1 : 0;
+    const int prune_sel = (flags & ALPA_DP_PRUNE) ? 1 : 0;
+    // Skipping a candidate while the recurrence runs is decided with one B; a sweep
+    // evaluates every candidate and applies the early-exit rule per B in the selection.
+    const int prune = n_B > 0 ? 0 : prune_sel;
     hipStream_t st = h->stream;
 
     HIPCHK(hipEventRecord(h->ev[0], st));
@@ -333,7 +477,34 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         }
     }
     HIPCHK(hipEventRecord(h->ev[2], st));
-    HIPCHK(launch_epilogue(st, p, h->d_cand, h->d_Fmin, h->d_Sbest, h->d_state, prune, h->d_T));
+    if (n_B > 0) {
+        HIPCHK(launch_sweep_epilogue(st, h->d_sw_B, n_B, &h->d_state->n_cand, h->d_cand, h->d_Fmin,
+                                     h->d_Sbest, h->d_sw_state, prune_sel, h->d_sw_c, h->d_sw_s));
+        if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
+            const size_t slab = (size_t)(p.Smax + 1) * (size_t)(p.K + 2) * (p.D + 1);
+            FastArgs fa{p, h->d_recs, h->d_sizes, h->d_sw_c, h->d_sw_n, h->d_sw_n + 1,
+                        &h->d_state->wave_relax, nullptr, 0, 0, h->d_sw_FS,
+                        h->d_sw_FS + (n_B + 1), n_B, h->d_sw_Fall, h->d_sw_s};
+            HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1, std::min(n_B, h->n_cu)));
+            HIPCHK(launch_plan_walk_many(st, p, h->d_table, h->d_sizes, h->d_sw_state,
+                                         h->d_sw_Fall, slab, h->d_sw_plans, n_B));
+        } else {
+            for (int b = 0; b < n_B; ++b) {        // one slab of layers, reused in stream order
+                SolveState *sb = h->d_sw_state + b;
+                HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, h->d_sw_c + b,
+                                                 &sb->plan_n, &sb->plan_ticket, nullptr, 0,
+                                                 h->d_tmpFS, h->d_tmpFS + 2, h->d_Fall,
+                                                 p.Smax + 1, 1));
+                HIPCHK(launch_plan_walk_many(st, p, h->d_table, h->d_sizes, sb, h->d_Fall, 0,
+                                             h->d_sw_plans + b, 1));
+            }
+        }
+        HIPCHK(hipEventRecord(h->ev[3], st));
+        h->any_solve = true;
+        h->timed = true;
+        return ALPA_DP_OK;
+    }
+    HIPCHK(launch_epilogue(st, p, h->d_cand, h->d_Fmin, h->d_Sbest, h->d_state, prune_sel, h->d_T));
     if (d_out_T && bound > 0)
         HIPCHK(launch_scatter_T(st, h->d_T, have_list ? h->d_rank : nullptr,
                                 have_list ? n_tmax : bound, h->d_state, d_out_T));
@@ -363,6 +534,34 @@ extern "C" int alpa_dp_solve_dev(alpa_dp_t *h, const int32_t *d_tmax, int n_tmax
     return solve_dev_impl(h, d_tmax, n_tmax, flags, d_out_T, d_out_plan, 31);
 }
 
+// Checks a host candidate list and queues its copy to the device; *d_tmax stays null if
+// there is none.
+static int stage_host_candidates(alpa_dp *h, const int32_t *tmax, int n_tmax,
+                                 const int32_t **d_tmax, int *key_bits)
+{
+    *d_tmax = nullptr;
+    *key_bits = 31;
+    if (tmax) {
+        if (n_tmax == 0) return fail(ALPA_DP_EINVAL, "empty candidate list");
+        int32_t mx = 0;
+        for (int j = 0; j < n_tmax; ++j) {
+            if (tmax[j] < 0 || tmax[j] == ALPA_DP_INF_I32)
+                return fail(ALPA_DP_EINVAL, "candidate out of range");
+            mx = std::max(mx, tmax[j]);
+        }
+        *key_bits = bits_for((uint32_t)mx);
+        if (n_tmax > h->cand_cap) {
+            HIPCHK(hipStreamSynchronize(h->stream));
+            int rc = alloc_candidate_arrays(h, n_tmax);
+            if (rc) return rc;
+        }
+        HIPCHK(hipMemcpyAsync(h->d_tmax_stage, tmax, (size_t)n_tmax * 4, hipMemcpyHostToDevice,
+                              h->stream));
+        *d_tmax = h->d_tmax_stage;
+    }
+    return ALPA_DP_OK;
+}
+
 extern "C" int alpa_dp_solve(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
                              int64_t *out_T, alpa_plan_t *out_plan)
 {
@@ -375,23 +574,9 @@ extern "C" int alpa_dp_solve(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsi
     if (prev != h->device) HIPCHK(hipSetDevice(h->device));
     struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
         restore{prev, h->device};
-    if (tmax) {
-        if (n_tmax == 0) return fail(ALPA_DP_EINVAL, "empty candidate list");
-        int32_t mx = 0;
-        for (int j = 0; j < n_tmax; ++j) {
-            if (tmax[j] < 0 || tmax[j] == ALPA_DP_INF_I32)
-                return fail(ALPA_DP_EINVAL, "candidate out of range");
-            mx = std::max(mx, tmax[j]);
-        }
-        key_bits = bits_for((uint32_t)mx);
-        if (n_tmax > h->cand_cap) {
-            HIPCHK(hipStreamSynchronize(h->stream));
-            int rc = alloc_candidate_arrays(h, n_tmax);
-            if (rc) return rc;
-        }
-        HIPCHK(hipMemcpyAsync(h->d_tmax_stage, tmax, (size_t)n_tmax * 4, hipMemcpyHostToDevice,
-                              h->stream));
-        d_tmax = h->d_tmax_stage;
+    {
+        int rc = stage_host_candidates(h, tmax, n_tmax, &d_tmax, &key_bits);
+        if (rc) return rc;
     }
     const int n_out = candidate_bound(h, tmax != nullptr, n_tmax);
     int rc = solve_dev_impl(h, d_tmax, n_tmax, flags, out_T ? h->d_outT_stage : nullptr,
@@ -406,6 +591,43 @@ extern "C" int alpa_dp_solve(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsi
     HIPCHK(hipStreamSynchronize(h->stream));
     if (out_plan && out_plan->num_stages < 0)
         return fail(ALPA_DP_EHIP, "internal inconsistency during plan recovery");
+    return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_solve_sweep(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
+                                   const int32_t *B_values, int n_B, alpa_plan_t *out_plans)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    if (n_tmax < 0) return fail(ALPA_DP_EINVAL, "n_tmax < 0");
+    if (!B_values || !out_plans) return fail(ALPA_DP_EINVAL, "B_values or out_plans is null");
+    if (n_B < 1 || n_B > ALPA_DP_MAX_SWEEP) return fail(ALPA_DP_EINVAL, "n_B out of range");
+    for (int b = 0; b < n_B; ++b)
+        if (B_values[b] < 1) return fail(ALPA_DP_EINVAL, "B must be >= 1");
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    int key_bits = 31;
+    const int32_t *d_tmax = nullptr;
+    int rc = stage_host_candidates(h, tmax, n_tmax, &d_tmax, &key_bits);
+    if (rc) return rc;
+    if (n_B > h->sw_cap) {
+        HIPCHK(hipStreamSynchronize(h->stream));
+        rc = alloc_sweep_arrays(h, n_B);
+        if (rc) return rc;
+    }
+    const int32_t head[2] = {n_B, 0};
+    HIPCHK(hipMemcpyAsync(h->d_sw_n, head, sizeof(head), hipMemcpyHostToDevice, h->stream));
+    HIPCHK(hipMemcpyAsync(h->d_sw_B, B_values, (size_t)n_B * 4, hipMemcpyHostToDevice, h->stream));
+    rc = solve_dev_impl(h, d_tmax, n_tmax, flags, nullptr, nullptr, key_bits, n_B);
+    if (rc) return rc;
+    HIPCHK(hipMemcpyAsync(out_plans, h->d_sw_plans, (size_t)n_B * sizeof(alpa_plan_t),
+                          hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    for (int b = 0; b < n_B; ++b)
+        if (out_plans[b].num_stages < 0)
+            return fail(ALPA_DP_EHIP, "internal inconsistency during plan recovery");
     return ALPA_DP_OK;
 }
 

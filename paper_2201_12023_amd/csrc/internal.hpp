@@ -126,6 +126,12 @@ hipError_t launch_set_candidates(hipStream_t st, const uint32_t *n_unique, Solve
 hipError_t launch_rank_lookup(hipStream_t st, const int32_t *tmax, int n, const int32_t *unique,
                               const uint32_t *n_unique, int32_t *rank_of_orig);
 
+// table[s-1][k][i][q] from profiled options [k][i][q][o]; *max_finite = largest finite entry
+// (-1 if none).  O * 1 KiB of LDS per block: O <= 32.
+hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t *mem_stage,
+                              const int64_t *mem_act, int K, int S, int O, int64_t mem_device,
+                              int32_t *table, int32_t *max_finite);
+
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
                               int32_t *recs);
 size_t fast_table_ints(int K, int S);    // size of the column-record array, padding included
@@ -144,8 +150,10 @@ struct FastArgs {
     int prune, descending;
     int32_t *Fmin, *Sbest;
     int dummy_idx;           // spare slot of Fmin / Sbest for the waves that own no result
-    int32_t *F_all;          // [Smax+1][(K+2)*(D+1)], plan mode only
-    const int32_t *s_top_p;  // plan mode only: number of stages of the winner (device memory)
+    // plan mode only: candidate j dumps its layers to F_all + j * (Smax+1) * (K+2)*(D+1) and
+    // stops at layer s_top_p[j], the winner's number of stages (device memory)
+    int32_t *F_all;
+    const int32_t *s_top_p;
 };
 enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);
@@ -159,6 +167,14 @@ hipError_t launch_scatter_T(hipStream_t st, const int64_t *T, const int32_t *ran
 hipError_t launch_plan_walk(hipStream_t st, const Problem &p, const int32_t *table,
                             const int32_t *sizes, SolveState *state, const int32_t *F_all,
                             void *plan_tmp, void *best_plan, void *plan_out);
+// sweep over B: one block per B value
+hipError_t launch_sweep_epilogue(hipStream_t st, const int32_t *B_vals, int n_B,
+                                 const int32_t *n_cand_p, const int32_t *cand,
+                                 const int32_t *Fmin, const int32_t *Sbest, SolveState *states,
+                                 int prune, int32_t *win_c, int32_t *win_s);
+hipError_t launch_plan_walk_many(hipStream_t st, const Problem &p, const int32_t *table,
+                                 const int32_t *sizes, SolveState *states, const int32_t *F_all,
+                                 size_t slab, void *plans, int n);
 hipError_t launch_init_state(hipStream_t st, SolveState *state, int64_t *chunk_min, int n_chunks);
 hipError_t launch_init_best_plan(hipStream_t st, void *best_plan);
 

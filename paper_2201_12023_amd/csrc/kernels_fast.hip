@@ -214,10 +214,12 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
         // Plan recovery walks back from F(s*, first layer 1, all devices): only layers up to
         // s* are needed, and of layer s only first layers (0-based) >= s* - s, since each of
         // the s* - s stages in front takes at least one layer.
-        const int s_top = DUMP ? min(p.Smax, __builtin_amdgcn_readfirstlane(*s_top_p)) : p.Smax;
+        const int s_top =
+            DUMP ? min(p.Smax, __builtin_amdgcn_readfirstlane(s_top_p[jj[0]])) : p.Smax;
+        int32_t *F_out = DUMP ? F_all + (size_t)jj[0] * (size_t)(p.Smax + 1) * LS : nullptr;
         if (DUMP) {
             const int total = (s_top + 1) * LS;
-            for (int x = tid; x < total; x += NT) F_all[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
+            for (int x = tid; x < total; x += NT) F_out[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
             __syncthreads();
         }
         int32_t best[NC], sbest[NC];
@@ -400,7 +402,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
             for (int e = 0; e < NC; ++e)
                 if (f1[e] < best[e]) { best[e] = f1[e]; sbest[e] = s; }   // lowest s on ties
             if (DUMP) {
-                int32_t *Fs = F_all + (size_t)s * LS;
+                int32_t *Fs = F_out + (size_t)s * LS;
                 if (WI == 1) {
 #pragma unroll
                     for (int u = 0; u < 16; ++u) {

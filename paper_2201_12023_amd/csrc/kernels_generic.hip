@@ -124,14 +124,13 @@ __global__ __launch_bounds__(256) void recurrence_generic_kernel(
 // is the prefix [0, p) where p is the first index with B * c_p >= min_{j < p} T(c_j), as
 // in the sequential loop of Alg. 1; the winner is the lowest T, lowest index on ties
 // (strict "<" of Alg. 1 while ascending).
-__global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t *__restrict__ cand,
-                                                        const int32_t *__restrict__ Fmin,
-                                                        const int32_t *__restrict__ Sbest,
-                                                        SolveState *state, int prune,
-                                                        int64_t *__restrict__ T)
+// `T` may be null (no per-candidate output).
+__device__ __forceinline__ void eq4_select(int B, int n, const int32_t *__restrict__ cand,
+                                           const int32_t *__restrict__ Fmin,
+                                           const int32_t *__restrict__ Sbest, SolveState *state,
+                                           int prune, int64_t *__restrict__ T)
 {
     const int lane = threadIdx.x;
-    const int n = state->n_cand;
     int64_t carry = INF_I64;          // min of T over all earlier chunks
     int n_proc = n;
     int64_t bestT = INF_I64;
@@ -141,8 +140,8 @@ __global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t
         int64_t t = INF_I64, bc = 0;
         if (j < n) {
             const int32_t f = Fmin[j], c = cand[j];
-            if (f < DEV_INF) t = (int64_t)f + (int64_t)(p.B - 1) * (int64_t)c;
-            bc = (int64_t)p.B * (int64_t)c;
+            if (f < DEV_INF) t = (int64_t)f + (int64_t)(B - 1) * (int64_t)c;
+            bc = (int64_t)B * (int64_t)c;
         }
         const int64_t incl = wave_prefix_min_i64(t, lane);
         // exclusive prefix minimum, including earlier chunks
@@ -154,7 +153,7 @@ __global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t
         const uint64_t fm = __ballot(fire);
         int limit = WAVE;                               // lanes below `limit` are processed
         if (fm) limit = __ffsll((unsigned long long)fm) - 1;
-        if (j < n) T[j] = (lane < limit) ? t : INF_I64;
+        if (T && j < n) T[j] = (lane < limit) ? t : INF_I64;
         // best among processed lanes of this chunk
         int64_t tt = (lane < limit && j < n) ? t : INF_I64;
         const int64_t m = wave_min_i64(tt);
@@ -166,7 +165,8 @@ __global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t
         if (fm) {
             n_proc = j0 + limit;
             // everything after the break is not evaluated
-            for (int x = j0 + WAVE + lane; x < n; x += WAVE) T[x] = INF_I64;
+            if (T)
+                for (int x = j0 + WAVE + lane; x < n; x += WAVE) T[x] = INF_I64;
             break;
         }
         carry = min64(carry, wave_min_i64(t));
@@ -180,6 +180,32 @@ __global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t
         state->plan_n = bestj >= 0 ? 1 : 0;
         state->plan_ticket = 0;
     }
+}
+
+__global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t *__restrict__ cand,
+                                                        const int32_t *__restrict__ Fmin,
+                                                        const int32_t *__restrict__ Sbest,
+                                                        SolveState *state, int prune,
+                                                        int64_t *__restrict__ T)
+{
+    eq4_select(p.B, state->n_cand, cand, Fmin, Sbest, state, prune, T);
+}
+
+// Sweep over the number of microbatches: F of Eq. 3 does not depend on B, so one wave per
+// B value applies Eq. 4 and the selection to the same Fmin / Sbest.  states[b] receives the
+// winner for B_vals[b]; win_c / win_s are the compact copies the plan-recovery run reads.
+__global__ __launch_bounds__(WAVE) void sweep_epilogue_kernel(
+    const int32_t *__restrict__ B_vals, const int32_t *__restrict__ n_cand_p,
+    const int32_t *__restrict__ cand, const int32_t *__restrict__ Fmin,
+    const int32_t *__restrict__ Sbest, SolveState *states, int prune, int32_t *__restrict__ win_c,
+    int32_t *__restrict__ win_s)
+{
+    const int b = blockIdx.x;
+    SolveState *st = states + b;
+    eq4_select(B_vals[b], *n_cand_p, cand, Fmin, Sbest, st, prune, nullptr);
+    __syncthreads();                                   // lane 0's stores, then every lane's reads
+    win_c[b] = st->best_c;                             // all lanes, same value
+    win_s[b] = st->best_s;
 }
 
 // out_T in the caller's order: out_T[j] = T[rank_of_orig[j]]
@@ -218,12 +244,17 @@ __global__ __launch_bounds__(WAVE) void plan_walk_kernel(Problem p, const int32_
                                                          const int32_t *__restrict__ sizes,
                                                          const SolveState *state,
                                                          const int32_t *__restrict__ F_all,
-                                                         PlanDev *plan, PlanDev *best_plan)
+                                                         size_t slab, PlanDev *plan,
+                                                         PlanDev *best_plan)
 {
+    // block b recovers the plan of states[b] from the layers at F_all + b * slab
     __shared__ PlanDev sh;
     const int lane = threadIdx.x;
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
+    state += blockIdx.x;
+    F_all += blockIdx.x * slab;
+    plan += blockIdx.x;
     const bool feasible = state->best_idx >= 0;
     const int32_t c = state->best_c;
     const int64_t T_new = state->best_T;
@@ -274,10 +305,11 @@ __global__ __launch_bounds__(WAVE) void plan_walk_kernel(Problem p, const int32_
         sh.n_evaluated = state->n_processed;
     }
     __syncthreads();
-    // running best over all solves of the handle: lower T*, then lower t_max
-    const int64_t bT = best_plan->T_star;
-    const int32_t bc = best_plan->t_max;
-    const bool better = good && (T_new < bT || (T_new == bT && c < bc));
+    // running best over all solves of the handle (not kept by sweeps: best_plan is null):
+    // lower T*, then lower t_max
+    const int64_t bT = best_plan ? best_plan->T_star : INF_I64;
+    const int32_t bc = best_plan ? best_plan->t_max : 0;
+    const bool better = best_plan && good && (T_new < bT || (T_new == bT && c < bc));
     const int n32 = (int)(sizeof(PlanDev) / 4);
     __syncthreads();
     for (int x = lane; x < n32; x += WAVE) {
@@ -360,10 +392,29 @@ hipError_t launch_plan_walk(hipStream_t st, const Problem &p, const int32_t *tab
                             void *plan_tmp, void *best_plan, void *plan_out)
 {
     hipLaunchKernelGGL(plan_walk_kernel, dim3(1), dim3(WAVE), 0, st, p, table, sizes, state, F_all,
-                       (PlanDev *)plan_tmp, (PlanDev *)best_plan);
+                       (size_t)0, (PlanDev *)plan_tmp, (PlanDev *)best_plan);
     if (plan_out && plan_out != plan_tmp)
         hipLaunchKernelGGL(copy_plan_kernel, dim3(1), dim3(256), 0, st, (const PlanDev *)plan_tmp,
                            (PlanDev *)plan_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_sweep_epilogue(hipStream_t st, const int32_t *B_vals, int n_B,
+                                 const int32_t *n_cand_p, const int32_t *cand,
+                                 const int32_t *Fmin, const int32_t *Sbest, SolveState *states,
+                                 int prune, int32_t *win_c, int32_t *win_s)
+{
+    hipLaunchKernelGGL(sweep_epilogue_kernel, dim3(n_B), dim3(WAVE), 0, st, B_vals, n_cand_p, cand,
+                       Fmin, Sbest, states, prune, win_c, win_s);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_walk_many(hipStream_t st, const Problem &p, const int32_t *table,
+                                 const int32_t *sizes, SolveState *states, const int32_t *F_all,
+                                 size_t slab, void *plans, int n)
+{
+    hipLaunchKernelGGL(plan_walk_kernel, dim3(n), dim3(WAVE), 0, st, p, table, sizes, states, F_all,
+                       slab, (PlanDev *)plans, (PlanDev *)nullptr);
     return hipGetLastError();
 }
 

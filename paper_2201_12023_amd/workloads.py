@@ -65,6 +65,7 @@ class Workload:
     layer_cost: np.ndarray = field(default=None)   # int64 [K], for the run log
     layer_mem: np.ndarray = field(default=None)    # int64 [K]
     layer_act: np.ndarray = field(default=None)    # int64 [K]
+    terms: dict = field(default=None)              # formula workloads: the table's ingredients
 
     @property
     def S(self) -> int:
@@ -97,7 +98,7 @@ _A2A_US = {1: 0, 2: 300, 4: 600, 8: 900, 16: 1200, 24: 1375, 32: 1500,
 
 
 def _formula_table(K, shapes, cost, mem, act_per_layer, cap, *, expert=None,
-                   act_mode="const"):
+                   act_mode="const", terms=None):
     """t(k..i, q, s) = ceil(sum c / a) + 50 (a - 1) + (n > 1 ? 400 : 0) [+ experts * a2a(a)],
     INF iff sum mem + s * act > cap * a  (integer-exact, no division)."""
     S = shapes.shape[0]
@@ -131,6 +132,8 @@ def _formula_table(K, shapes, cost, mem, act_per_layer, cap, *, expert=None,
     feas = need <= (cap * a)[None, None, None, :]
     table = np.where(feas & valid[None, :, :, None], lat[None, :, :, :], int(INF_I32))
     assert table[table != int(INF_I32)].max() < 2**30
+    if terms is not None:
+        terms.update(lat=lat, msum=msum, actv=actv, cap=int(cap), a=a, valid=valid)
     return np.ascontiguousarray(table.astype(np.int32))
 
 
@@ -144,9 +147,10 @@ def make_workload(idx: int) -> Workload:
         for l in range(K):
             cost[l] = rng.uint(200, 2000); mem[l] = rng.uint(1, 8)
         shapes = submesh_shapes(N, M)
-        table = _formula_table(K, shapes, cost, mem, 1, 16)
+        terms = {}
+        table = _formula_table(K, shapes, cost, mem, 1, 16, terms=terms)
         return Workload("tiny", K, N, M, B, shapes, table, "all", 0, False, seed,
-                        cost, mem, np.full(K, 1, np.int64))
+                        cost, mem, np.full(K, 1, np.int64), terms)
     if idx == 2:
         K, N, M, B, seed = 24, 2, 8, 32, 1
         rng = SplitMix64(seed)
@@ -154,9 +158,10 @@ def make_workload(idx: int) -> Workload:
         for l in range(K):
             cost[l] = rng.uint(900, 1100); mem[l] = rng.uint(3, 5)
         shapes = submesh_shapes(N, M)
-        table = _formula_table(K, shapes, cost, mem, 2, 80)
+        terms = {}
+        table = _formula_table(K, shapes, cost, mem, 2, 80, terms=terms)
         return Workload("gpt", K, N, M, B, shapes, table, "all", 0, True, seed,
-                        cost, mem, np.full(K, 2, np.int64))
+                        cost, mem, np.full(K, 2, np.int64), terms)
     if idx == 3:
         K, N, M, B, seed = 48, 8, 8, 64, 2
         rng = SplitMix64(seed)
@@ -164,9 +169,10 @@ def make_workload(idx: int) -> Workload:
         for l in range(K):
             cost[l] = rng.uint(1800, 2200); mem[l] = rng.uint(6, 10)
         shapes = submesh_shapes(N, M)
-        table = _formula_table(K, shapes, cost, mem, 4, 80)
+        terms = {}
+        table = _formula_table(K, shapes, cost, mem, 4, 80, terms=terms)
         return Workload("large", K, N, M, B, shapes, table, "quantiles", 4096, False, seed,
-                        cost, mem, np.full(K, 4, np.int64))
+                        cost, mem, np.full(K, 4, np.int64), terms)
     if idx == 4:
         K, N, M, B, seed = 64, 8, 8, 128, 3
         rng = SplitMix64(seed)
@@ -179,9 +185,10 @@ def make_workload(idx: int) -> Workload:
                 cost[l] = rng.uint(2000, 2800); mem[l] = rng.uint(16, 24)
                 expert[l] = 1
         shapes = submesh_shapes(N, M)
-        table = _formula_table(K, shapes, cost, mem, 3, 80, expert=expert)
+        terms = {}
+        table = _formula_table(K, shapes, cost, mem, 3, 80, expert=expert, terms=terms)
         return Workload("moe", K, N, M, B, shapes, table, "quantiles", 4096, False, seed,
-                        cost, mem, np.full(K, 3, np.int64))
+                        cost, mem, np.full(K, 3, np.int64), terms)
     if idx == 5:
         K, N, M, B, seed = 64, 8, 8, 32, 4
         rng = SplitMix64(seed)
@@ -191,9 +198,10 @@ def make_workload(idx: int) -> Workload:
             mem[l] = _round_half_away(1.0 + 0.5 * 1.06 ** l)
             act[l] = _round_half_away(12.0 * 0.95 ** l)
         shapes = submesh_shapes(N, M)
-        table = _formula_table(K, shapes, cost, mem, act, 80, act_mode="max")
+        terms = {}
+        table = _formula_table(K, shapes, cost, mem, act, 80, act_mode="max", terms=terms)
         return Workload("wrn", K, N, M, B, shapes, table, "all", 0, False, seed,
-                        cost, mem, act)
+                        cost, mem, act, terms)
     raise ValueError("workload index must be 1..5")
 
 
@@ -221,3 +229,80 @@ def random_problem(seed: int, K: int, N: int, M: int, *, S_extra_dup: bool = Fal
         B = int(rng.integers(1, 9))
     return Workload(f"rand{seed}", K, N, M, B, shapes.astype(np.int32),
                     np.ascontiguousarray(table.astype(np.int32)), "all", 0, False, seed)
+
+
+# ---------------------------------------------------------------------------------------------
+# Profiled options: the inputs of the table-construction step (Sec. 5.2, Eq. 5; Alg. 1's
+# "run the intra-op pass" loop nest).  Only inputs are made here; the step itself (pick the
+# fastest option that fits, per s) is in the oracle and in the HIP library.
+
+@dataclass
+class Profiles:
+    K: int
+    S: int
+    O: int
+    t_l: np.ndarray             # int32 [K, K, S, O] microseconds, INF = option absent
+    mem_stage: np.ndarray       # int64 [K, K, S, O] bytes per device
+    mem_act: np.ndarray         # int64 [K, K, S, O] bytes per device and in-flight microbatch
+    mem_device: int             # bytes
+
+
+def single_option_profiles(w: Workload) -> Profiles:
+    """One option per (stage, submesh) whose figures restate a formula workload: the workload's
+    rule "sum mem + s * act <= cap * a" becomes "mem_stage + s * mem_act <= mem_device" with
+    mem_stage = sum mem + (BIG - cap * a), mem_act = act, mem_device = BIG."""
+    t = w.terms
+    K, S = w.K, w.S
+    big = int(t["cap"]) * int(t["a"].max())
+    valid = t["valid"][:, :, None, None]
+    t_l = np.where(valid, t["lat"][:, :, :, None], int(INF_I32)).astype(np.int32)
+    mem_stage = (t["msum"][:, :, None] + (big - t["cap"] * t["a"])[None, None, :])[..., None]
+    mem_act = np.broadcast_to(t["actv"][:, :, None, None], (K, K, S, 1))
+    return Profiles(K, S, 1, np.ascontiguousarray(t_l),
+                    np.ascontiguousarray(mem_stage.astype(np.int64)),
+                    np.ascontiguousarray(mem_act.astype(np.int64)), big)
+
+
+def make_profiles(idx: int, n_options: int = 6) -> Profiles:
+    """Several options per (stage, submesh) for formula workload ``idx``: option o is slower and
+    leaner than option o - 1 (more sharding / rematerialisation): latency x (100 + 9 o + U[0,5]) %,
+    memory x (16 - 2 o) / 16 with a floor of 1/4, in bytes per device (1 MiB units, ceil-divided by
+    the device count); about 8 % of the options are absent.  mem_device = cap MiB."""
+    w = make_workload(idx)
+    t = w.terms
+    K, S, O = w.K, w.S, int(n_options)
+    rng = np.random.default_rng(1000 + w.seed)
+    a = t["a"].astype(np.int64)
+    lat = t["lat"].astype(np.int64)[:, :, :, None]                              # [K,K,S,1]
+    o = np.arange(O, dtype=np.int64)[None, None, None, :]
+    jitter = rng.integers(0, 6, size=(K, K, S, O), dtype=np.int64)
+    t_l = lat * (100 + 9 * o + jitter) // 100
+    absent = rng.random(size=(K, K, S, O)) < 0.08
+    valid = t["valid"][:, :, None, None]
+    t_l = np.where(valid & ~absent, t_l, int(INF_I32)).astype(np.int32)
+    lean = np.maximum(16 - 2 * o, 4)                                            # sixteenths
+    mib = 1 << 20
+    ms = t["msum"].astype(np.int64)[:, :, None, None] * mib * lean              # x16, all devices
+    ma = t["actv"].astype(np.int64)[:, :, None, None] * mib * lean
+    div = 16 * a[None, None, :, None]
+    mem_stage = (ms + div - 1) // div
+    mem_act = np.broadcast_to((ma + div - 1) // div, (K, K, S, O))
+    return Profiles(K, S, O, np.ascontiguousarray(t_l), np.ascontiguousarray(mem_stage),
+                    np.ascontiguousarray(mem_act), int(t["cap"]) * mib)
+
+
+def random_profiles(seed: int, K: int, S: int, O: int, *, absent_frac: float = 0.2) -> Profiles:
+    """Unstructured profiles: every figure drawn independently, many ties, zero activation
+    sizes, options absent with probability ``absent_frac``, and a device size in the middle of
+    the range of requirements so that the fitting set changes with s."""
+    rng = np.random.default_rng(seed)
+    t_l = rng.integers(1, 60, size=(K, K, S, O), dtype=np.int64)
+    t_l[rng.random(size=t_l.shape) < absent_frac] = int(INF_I32)
+    kk = np.arange(K)[:, None]
+    ii = np.arange(K)[None, :]
+    t_l[ii < kk] = int(INF_I32)
+    mem_stage = rng.integers(0, 40, size=t_l.shape, dtype=np.int64)
+    mem_act = rng.integers(0, 6, size=t_l.shape, dtype=np.int64)
+    mem_device = int(rng.integers(20, 40 + 3 * K))
+    return Profiles(K, S, O, np.ascontiguousarray(t_l.astype(np.int32)), mem_stage, mem_act,
+                    mem_device)

@@ -6,7 +6,11 @@ the plan Alg. 1 ends with, as computed by ``oracle/`` (thread-per-candidate driv
 large ones).  Stored: counts, SHA-256 of the int32 candidate array and of the int64 T array
 (little endian), every 97th T value, and the plan.  Nothing here touches the HIP library.
 
-Run from the repository root:  python tests/golden/make_golden.py [workload numbers]
+With ``--sweep`` it writes tests/golden/sweep_<n>.json instead: the plan Alg. 1 ends with for
+each of several numbers of microbatches B (Sec. 5.2: B is found by enumeration), every one a
+separate run of the oracle.
+
+Run from the repository root:  python tests/golden/make_golden.py [--sweep] [workload numbers]
 """
 import hashlib
 import json
@@ -54,5 +58,37 @@ def main(which):
               f"{out['oracle_seconds']} s", flush=True)
 
 
+SWEEP_B = [1, 8, 32, 128, 512]
+
+
+def main_sweep(which):
+    threads = int(os.environ.get("ORACLE_THREADS", "8"))
+    for idx in which:
+        w = W.make_workload(idx)
+        t0 = time.time()
+        cand = oracle.all_candidates(w.table, w.shapes)
+        if w.candidates == "quantiles":
+            cand = oracle.quantiles(cand, w.n_quantiles)
+        plans = []
+        for Bv in SWEEP_B:
+            _, plan = oracle.solve_parallel(w.table, w.N, w.M, Bv, w.shapes, cand, w.prune, threads)
+            plans.append(dict(B=Bv, T_star=plan.T_star, t_max=plan.t_max,
+                              num_stages=plan.num_stages, n_evaluated=plan.n_evaluated,
+                              first_layer=plan.first_layer, shape_idx=plan.shape_idx))
+            print(f"workload {idx} B={Bv}: T*={plan.T_star} t_max={plan.t_max} "
+                  f"stages={plan.num_stages}", flush=True)
+        out = dict(workload=idx, prune=bool(w.prune), n_candidates=int(cand.size),
+                   table_sha256=hashlib.sha256(w.table.tobytes()).hexdigest(), plans=plans,
+                   oracle_seconds=round(time.time() - t0, 2), oracle_threads=threads)
+        path = os.path.join(ROOT, "tests", "golden", f"sweep_{idx}.json")
+        with open(path, "w") as f:
+            json.dump(out, f, indent=1)
+            f.write("\n")
+
+
 if __name__ == "__main__":
-    main([int(a) for a in sys.argv[1:]] or [1, 2, 3, 4, 5])
+    args = sys.argv[1:]
+    if "--sweep" in args:
+        main_sweep([int(a) for a in args if a != "--sweep"] or [3, 4, 5])
+    else:
+        main([int(a) for a in args] or [1, 2, 3, 4, 5])

@@ -71,6 +71,9 @@ def test_null_handle_is_rejected():
     L = B.load()
     assert L.alpa_dp_solve(None, None, 0, 0, None, None) == -1
     assert L.alpa_dp_solve_dev(None, None, 0, 0, None, None) == -1
+    Bs = np.asarray([1, 2], np.int32)
+    out = (B.alpa_plan_t * 2)()
+    assert L.alpa_dp_solve_sweep(None, None, 0, 0, Bs.ctypes.data, 2, ctypes.addressof(out)) == -1
     assert L.alpa_dp_best(None, None) == -1
     assert L.alpa_dp_set_B(None, 3) == -1
     L.alpa_dp_destroy(None)
