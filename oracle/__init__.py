@@ -1,4 +1,5 @@
-"""ctypes wrapper around the CPU oracle (``alpa_dp_oracle.c``, ``alpa_table_oracle.c``).
+"""ctypes wrapper around the CPU oracle (``alpa_dp_oracle.c``, ``alpa_table_oracle.c``,
+``alpa_cluster_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, the smoke check and the
 benchmark's ``cpu_baseline`` leg.  It never imports the HIP package and the HIP
@@ -23,6 +24,8 @@ _SRC = os.path.join(_HERE, "alpa_dp_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _SRC_TABLE = os.path.join(_HERE, "alpa_table_oracle.c")
 _LIB_TABLE = os.path.join(_HERE, "libtable_oracle.so")
+_SRC_CLUSTER = os.path.join(_HERE, "alpa_cluster_oracle.c")
+_LIB_CLUSTER = os.path.join(_HERE, "libcluster_oracle.so")
 
 INF64 = np.iinfo(np.int64).max
 INF32 = np.iinfo(np.int32).max
@@ -31,7 +34,7 @@ MAX_K = 256
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, -O2, no threads)."""
-    for src, out in ((_SRC, _LIB), (_SRC_TABLE, _LIB_TABLE)):
+    for src, out in ((_SRC, _LIB), (_SRC_TABLE, _LIB_TABLE), (_SRC_CLUSTER, _LIB_CLUSTER)):
         if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
             subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall",
                                    "-o", out, src])
@@ -99,6 +102,32 @@ def build_table(t_l, mem_stage, mem_act, mem_device: int) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"orc_build_table failed: {rc}")
     return table
+
+
+_lib_cluster = None
+
+
+def cluster(flop, src, dst, nbytes, L: int, delta_ppm: int):
+    """Operator clustering (Eq. 6).  Returns (G, V, first_op list of L + 1) or (INF64, 0, [])."""
+    global _lib_cluster
+    if _lib_cluster is None:
+        build()
+        _lib_cluster = ctypes.CDLL(_LIB_CLUSTER)
+    flop = np.ascontiguousarray(flop, dtype=np.int32)
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    dst = np.ascontiguousarray(dst, dtype=np.int32)
+    nbytes = np.ascontiguousarray(nbytes, dtype=np.int64)
+    assert src.size == dst.size == nbytes.size
+    G, V = ctypes.c_int64(), ctypes.c_int64()
+    first = np.zeros(int(L) + 1, dtype=np.int32)
+    rc = _lib_cluster.orc_cluster(_i32p(flop), _i32p(src), _i32p(dst), _i64p(nbytes),
+                                  int(src.size), int(flop.size), int(L), int(delta_ppm),
+                                  ctypes.byref(G), ctypes.byref(V), _i32p(first))
+    if rc != 0:
+        raise RuntimeError(f"orc_cluster failed: {rc}")
+    if G.value == INF64:
+        return INF64, 0, []
+    return int(G.value), int(V.value), [int(x) for x in first]
 
 
 def _i32p(a):

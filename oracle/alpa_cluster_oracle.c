@@ -1,0 +1,117 @@
+/*
+ * CPU oracle for the operator-clustering dynamic program of the inter-operator pass.
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, single-threaded
+ * statement of what the step computes, written from the paper; only tests, the
+ * smoke check and the benchmark's cpu-baseline leg may call it.  It shares no
+ * code, header, table or helper with the HIP library.
+ *
+ * What is followed (Sec. 5.2, "performance optimization #2: operator
+ * clustering", Eq. 6): operators o_1..o_K in topological order are cut into L
+ * consecutive layers.  G(k, r) is the smallest possible value of the largest
+ * amount of data any one layer receives when o_1..o_k form r layers:
+ *     G(k, r) = min over 1 <= i <= k with
+ *                   FLOP(o_i..o_k) <= (1 + delta) * FLOP_total / L
+ *               of max{ G(i - 1, r - 1), C(i, k) },
+ * C(i, k) = total size of the inputs that o_i..o_k receive from o_1..o_{i-1}.
+ * Among choices with the same value the one with the more uniform per-layer
+ * FLOP is taken.
+ *
+ * Readings taken where the paper is silent:
+ *   - the graph is an edge list (producer, consumer, bytes), producer before
+ *     consumer; C(i, k) sums the edges with producer < i <= consumer <= k (every
+ *     edge counts, also two edges from one producer);
+ *   - G(0, 0) = 0 and every other G(., 0), G(0, .) is +infinity; a layer holds at
+ *     least one operator;
+ *   - "minimising the variance" with L and the total fixed is minimising the sum
+ *     of squared per-layer FLOP; it is carried as a second component V(k, r) and
+ *     used as the tie-break inside the recurrence (cell by cell, as the
+ *     recurrence is stated), then the lowest i;
+ *   - delta is given in parts per million and the FLOP condition is evaluated in
+ *     integers: FLOP(i..k) * L * 10^6 <= (10^6 + delta_ppm) * FLOP_total;
+ *   - FLOP figures are int32 in the caller's unit with a total below 2^31, byte
+ *     counts int64; all sums int64.
+ * Operators are 0-based in the arrays: first_op[r] is the first operator of
+ * layer r, first_op[L] = K.
+ *
+ * Parity pins (tests marked "not gpu"): a hand-worked example stored under
+ * tests/golden/, enumeration of every clustering for K <= 10 (the first
+ * component is the true optimum; on chain graphs, where every cut costs the
+ * same, so is the second), closed forms (L = 1, L = K, one heavy operator),
+ * and invariants.  For general graphs the second component is the recurrence's
+ * own tie-break, not a global optimum: it is pinned only through the properties
+ * above ("parity partially pinned").
+ */
+#include <stdint.h>
+#include <stdlib.h>
+
+#define ORC_INF64 INT64_MAX
+
+/* C(i, k), 1-based, by the definition: one pass over the edge list per cell */
+static int64_t comm_in(const int32_t *src, const int32_t *dst, const int64_t *bytes, int E,
+                       int i, int k)
+{
+    int64_t sum = 0;
+    for (int e = 0; e < E; ++e) {
+        const int u = src[e] + 1, v = dst[e] + 1;          /* 1-based operators */
+        if (u < i && i <= v && v <= k) sum += bytes[e];
+    }
+    return sum;
+}
+
+int orc_cluster(const int32_t *flop, const int32_t *src, const int32_t *dst,
+                const int64_t *bytes, int E, int K, int L, int delta_ppm,
+                int64_t *out_G, int64_t *out_V, int32_t *first_op)
+{
+    if (K < 1 || L < 1 || delta_ppm < 0 || E < 0) return -1;
+    int64_t total = 0;
+    for (int k = 0; k < K; ++k) {
+        if (flop[k] < 0) return -1;
+        total += flop[k];
+    }
+    if (total >= ((int64_t)1 << 31)) return -1;
+    for (int e = 0; e < E; ++e)
+        if (src[e] < 0 || dst[e] >= K || src[e] >= dst[e] || bytes[e] < 0) return -1;
+
+    const size_t W = (size_t)K + 1;
+    int64_t *C = malloc(W * W * sizeof(int64_t));
+    int64_t *G = malloc((size_t)(L + 1) * W * sizeof(int64_t));
+    int64_t *V = malloc((size_t)(L + 1) * W * sizeof(int64_t));
+    int32_t *A = malloc((size_t)(L + 1) * W * sizeof(int32_t));
+    if (!C || !G || !V || !A) { free(C); free(G); free(V); free(A); return -2; }
+    for (int i = 1; i <= K; ++i)
+        for (int k = i; k <= K; ++k) C[i * W + k] = comm_in(src, dst, bytes, E, i, k);
+    for (int r = 0; r <= L; ++r)
+        for (int k = 0; k <= K; ++k) { G[r * W + k] = ORC_INF64; V[r * W + k] = 0; A[r * W + k] = 0; }
+    G[0] = 0;
+    for (int r = 1; r <= L; ++r)
+        for (int k = 1; k <= K; ++k) {
+            int64_t bg = ORC_INF64, bv = 0;
+            int bi = 0;
+            for (int i = 1; i <= k; ++i) {
+                int64_t f = 0;
+                for (int x = i; x <= k; ++x) f += flop[x - 1];
+                if (f * (int64_t)L * 1000000 > ((int64_t)1000000 + delta_ppm) * total) continue;
+                const int64_t gp = G[(r - 1) * W + (i - 1)];
+                if (gp == ORC_INF64) continue;
+                const int64_t c = C[i * W + k];
+                const int64_t g = gp > c ? gp : c;
+                const int64_t v = V[(r - 1) * W + (i - 1)] + f * f;
+                if (g < bg || (g == bg && v < bv)) { bg = g; bv = v; bi = i; }
+            }
+            G[r * W + k] = bg; V[r * W + k] = bv; A[r * W + k] = bi;
+        }
+    *out_G = G[L * W + K];
+    *out_V = G[L * W + K] == ORC_INF64 ? 0 : V[L * W + K];
+    if (G[L * W + K] != ORC_INF64) {
+        int k = K;
+        first_op[L] = K;
+        for (int r = L; r >= 1; --r) {
+            const int i = A[r * W + k];
+            first_op[r - 1] = i - 1;
+            k = i - 1;
+        }
+    }
+    free(C); free(G); free(V); free(A);
+    return 0;
+}

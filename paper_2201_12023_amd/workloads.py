@@ -306,3 +306,59 @@ def random_profiles(seed: int, K: int, S: int, O: int, *, absent_frac: float = 0
     mem_device = int(rng.integers(20, 40 + 3 * K))
     return Profiles(K, S, O, np.ascontiguousarray(t_l.astype(np.int32)), mem_stage, mem_act,
                     mem_device)
+
+
+# ---------------------------------------------------------------------------------------------
+# Operator graphs: the inputs of the operator-clustering step (Sec. 5.2, Eq. 6).  Inputs only.
+
+@dataclass
+class OpGraph:
+    K: int
+    flop: np.ndarray            # int32 [K], caller's unit (here MFLOP), total < 2^31
+    src: np.ndarray             # int32 [E] producer (0-based), src < dst
+    dst: np.ndarray             # int32 [E] consumer
+    nbytes: np.ndarray          # int64 [E]
+
+
+def make_op_graph(seed: int, n_blocks: int) -> OpGraph:
+    """Flattened transformer-like graph: an embedding, ``n_blocks`` blocks of 12 operators
+    (norm, qkv, scores, softmax, context, proj, add, norm, mlp-up, gelu, mlp-down, add) and a
+    head.  Matrix products carry the FLOP (with +-10 % jitter), element-wise operators almost
+    none; every operator feeds the next one with an activation-sized tensor (the score tensors
+    are 4x larger), and each residual ``add`` also reads the block's input (a skip edge)."""
+    rng = np.random.default_rng(seed)
+    act = 8 << 20                                     # bytes of one activation tensor
+    heavy = {1: 3000, 2: 500, 4: 500, 5: 1000, 8: 4000, 10: 4000}
+    flop, src, dst, nb = [40], [], [], []            # embedding
+    for b in range(n_blocks):
+        base = len(flop)
+        for j in range(12):
+            f = heavy.get(j, 2)
+            flop.append(int(f * (0.9 + 0.2 * rng.random())) if f > 2 else int(rng.integers(1, 4)))
+            src.append(base + j - 1)
+            dst.append(base + j)
+            nb.append(act * (4 if j in (3, 4) else 1) + int(rng.integers(0, 4096)))
+        # residual connections: block input -> first add, first add -> second add
+        src += [base - 1, base + 6]
+        dst += [base + 6, base + 11]
+        nb += [act, act]
+        # qkv output is also read by the context product
+        src.append(base + 1); dst.append(base + 4); nb.append(act)
+    flop.append(2500)                                 # head
+    src.append(len(flop) - 2); dst.append(len(flop) - 1); nb.append(act)
+    return OpGraph(len(flop), np.asarray(flop, np.int32), np.asarray(src, np.int32),
+                   np.asarray(dst, np.int32), np.asarray(nb, np.int64))
+
+
+def random_op_graph(seed: int, K: int, E: int, *, flop_hi: int = 9, bytes_hi: int = 6) -> OpGraph:
+    """Unstructured graph: independent FLOP figures (zeros allowed), E random forward edges
+    (parallel edges allowed) with small byte counts, so ties are frequent."""
+    rng = np.random.default_rng(seed)
+    flop = rng.integers(0, flop_hi + 1, size=K).astype(np.int32)
+    if K >= 2 and E > 0:
+        u = rng.integers(0, K - 1, size=E)
+        v = u + 1 + (rng.integers(0, K, size=E) % (K - 1 - u))
+        nb = rng.integers(0, bytes_hi + 1, size=E)
+    else:
+        u = v = nb = np.zeros(0, np.int64)
+    return OpGraph(K, flop, u.astype(np.int32), v.astype(np.int32), nb.astype(np.int64))
