@@ -224,6 +224,37 @@ void alpa_dp_destroy(alpa_dp_t *h);
 /* Message of the calling thread's last failed call ("" if none).  Never NULL. */
 const char *alpa_dp_last_error(void);
 
+/*
+ * Operator clustering (Sec. 5.2, performance optimisation #2, Eq. 6): cut the operators
+ * o_1..o_K (topological order) into L consecutive layers so that the largest amount of data
+ * any layer receives from earlier operators is smallest,
+ *   G(k, r) = min over 1 <= i <= k with FLOP(o_i..o_k) <= (1 + delta) FLOP_total / L
+ *             of max{G(i-1, r-1), C(i, k)},
+ * ties going to the smaller sum of squared per-layer FLOP (the lower variance), then to the
+ * smaller i, cell by cell.  Stateless; runs on the calling thread's current device, null
+ * stream; blocking.  All pointers are HOST pointers, read / written during the call only.
+ *
+ *   flop          int32 [K], >= 0, any unit; total < 2^31 and total * L < 2^42.
+ *   edge_src/dst  int32 [num_edges], 0-based operators, src < dst; parallel edges add up.
+ *   edge_bytes    int64 [num_edges], >= 0, sum < 2^62.
+ *   delta_ppm     delta in parts per million, 0..10^9; the FLOP condition is evaluated in
+ *                 integers: FLOP(i..k) * L * 10^6 <= (10^6 + delta_ppm) * total.
+ *   *out_comm     G(K, L), or ALPA_DP_INF_I64 if no clustering satisfies the FLOP bound
+ *                 (then *out_sumsq = 0 and out_first_op[] = -1).
+ *   *out_sumsq    sum of squared per-layer FLOP of the clustering returned.
+ *   out_first_op  int32 [L + 1]: layer r = operators [out_first_op[r], out_first_op[r+1]).
+ *   out_ms        NULL, or receives the device time of the kernels (HIP events).
+ *
+ * Errors: EINVAL (null pointer, K or L outside 1..ALPA_CLUSTER_MAX_OPS, bad edge, negative
+ * figure, delta_ppm out of range), EOVERFLOW (the limits above), ENOMEM (8 K^2 + 4 L K bytes
+ * of device memory are needed), EHIP.
+ */
+#define ALPA_CLUSTER_MAX_OPS 4096
+int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
+                        const int32_t *edge_dst, const int64_t *edge_bytes, int num_edges,
+                        int L, int delta_ppm, int64_t *out_comm, int64_t *out_sumsq,
+                        int32_t *out_first_op, float *out_ms);
+
 #ifdef __cplusplus
 }
 #endif

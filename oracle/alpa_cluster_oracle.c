@@ -70,6 +70,7 @@ int orc_cluster(const int32_t *flop, const int32_t *src, const int32_t *dst,
         total += flop[k];
     }
     if (total >= ((int64_t)1 << 31)) return -1;
+    if (total * (int64_t)L >= ((int64_t)1 << 42)) return -1;   /* keeps the FLOP test inside int64 */
     for (int e = 0; e < E; ++e)
         if (src[e] < 0 || dst[e] >= K || src[e] >= dst[e] || bytes[e] < 0) return -1;
 

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libalpa_dp.so")
 MAX_K = 256
 MAX_SWEEP = 256
 MAX_OPTIONS = 32
+CLUSTER_MAX_OPS = 4096
 INF_I32 = 2**31 - 1
 INF_I64 = 2**63 - 1
 ALPA_DP_PRUNE = 1
@@ -28,7 +29,7 @@ SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table"
            "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
            "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
-           "alpa_dp_last_error"]
+           "alpa_dp_last_error", "alpa_cluster_layers"]
 
 
 class alpa_shape_t(ctypes.Structure):
@@ -89,6 +90,9 @@ def load():
     L.alpa_dp_best.argtypes = [vp, ctypes.POINTER(alpa_plan_t)]
     L.alpa_dp_last_timing.argtypes = [vp] + [ctypes.POINTER(ctypes.c_float)] * 3
     L.alpa_dp_last_counters.argtypes = [vp, ctypes.POINTER(ctypes.c_int), i64p]
+    L.alpa_cluster_layers.argtypes = [vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int, i64p, i64p, vp,
+                                      ctypes.POINTER(ctypes.c_float)]
     L.alpa_dp_destroy.argtypes = [vp]
     L.alpa_dp_destroy.restype = None
     L.alpa_dp_last_error.restype = ctypes.c_char_p
@@ -238,3 +242,25 @@ def plan_from_bytes(buf: bytes) -> dict:
 
 
 PLAN_BYTES = ctypes.sizeof(alpa_plan_t)
+
+
+def alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm):
+    """Operator clustering (Eq. 6).  Host arrays in; returns dict(comm, sumsq, first_op, ms);
+    comm == INF_I64 and first_op == [] if no clustering satisfies the FLOP bound."""
+    lib = load()
+    f = np.ascontiguousarray(flop, dtype=np.int32)
+    s = np.ascontiguousarray(edge_src, dtype=np.int32)
+    d = np.ascontiguousarray(edge_dst, dtype=np.int32)
+    b = np.ascontiguousarray(edge_bytes, dtype=np.int64)
+    if not (s.size == d.size == b.size):
+        raise ValueError("edge arrays must have one length")
+    comm, sumsq, ms = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_float()
+    first = np.zeros(max(int(L), 0) + 1, dtype=np.int32)
+    _check(lib.alpa_cluster_layers(f.ctypes.data, int(f.size), s.ctypes.data if s.size else None,
+                                   d.ctypes.data if s.size else None,
+                                   b.ctypes.data if s.size else None, int(s.size), int(L),
+                                   int(delta_ppm), ctypes.byref(comm), ctypes.byref(sumsq),
+                                   first.ctypes.data, ctypes.byref(ms)))
+    feasible = comm.value != INF_I64
+    return {"comm": int(comm.value), "sumsq": int(sumsq.value),
+            "first_op": [int(x) for x in first] if feasible else [], "ms": float(ms.value)}

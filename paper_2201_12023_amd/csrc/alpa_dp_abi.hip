@@ -23,6 +23,12 @@ static int fail(int code, const std::string &msg)
     return code;
 }
 
+// for the library's other translation units: same thread-local message
+extern "C" __attribute__((visibility("hidden"))) int alpa_dp_set_error_(int code, const char *msg)
+{
+    return fail(code, msg);
+}
+
 #define HIPCHK(expr)                                                                        \
     do {                                                                                    \
         hipError_t e_ = (expr);                                                             \

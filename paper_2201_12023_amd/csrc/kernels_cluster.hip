@@ -1,0 +1,250 @@
+// Operator clustering on the device (Sec. 5.2, performance optimisation #2, Eq. 6):
+//   G(n, r) = min over 1 <= i <= n with FLOP(o_i..o_n) <= cap of max{G(i-1, r-1), C(i, n)},
+// C(i, n) = bytes that o_i..o_n receive from o_1..o_{i-1}; ties go to the smaller sum of squared
+// per-layer FLOP (carried as V(n, r)), then to the smaller i.
+//
+// Kernels: the edge list is added into a dense consumer-major matrix; an exclusive prefix along
+// producers and a running sum down consumers turn it, in place, into Ct[n][i] = C(i, n) with
+// the candidates i of one n contiguous; one launch per r then evaluates every n in parallel,
+// one wave per n, lanes over i, with a lexicographic wave minimum; one thread walks the stored
+// arg-minima back.  FLOP figures are non-negative, so the feasible i of an n form a suffix
+// [i_min(n), n] found by bisection on the FLOP prefix sums: the work is K * (layer length) per r,
+// not K^2.  Memory-bound on the reads of Ct.
+#include "internal.hpp"
+
+namespace alpa {
+
+constexpr int CL_TILE = 64;            // rows per chunk of the column scan
+
+// pf[x] = FLOP of operators 0..x-1 (int64), one block
+__global__ __launch_bounds__(1024) void flop_prefix_kernel(const int32_t *__restrict__ flop, int K,
+                                                           int64_t *__restrict__ pf)
+{
+    __shared__ int64_t part[1024];
+    const int t = threadIdx.x;
+    const int per = (K + 1023) / 1024;
+    const int lo = min(K, t * per), hi = min(K, lo + per);
+    int64_t s = 0;
+    for (int x = lo; x < hi; ++x) s += flop[x];
+    part[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        const int64_t o = (t >= off) ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    int64_t run = part[t] - s;
+    if (t == 0) pf[0] = 0;
+    for (int x = lo; x < hi; ++x) {
+        run += flop[x];
+        pf[x + 1] = run;
+    }
+}
+
+__global__ void zero_i64_kernel(int64_t *p, long long n)
+{
+    for (long long x = blockIdx.x * (long long)blockDim.x + threadIdx.x; x < n;
+         x += (long long)gridDim.x * blockDim.x)
+        p[x] = 0;
+}
+
+// Wt[v][u] += bytes(u -> v)
+__global__ void edges_to_matrix_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ dst,
+                                       const int64_t *__restrict__ nbytes, int E, int K,
+                                       int64_t *__restrict__ Wt)
+{
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < E; e += gridDim.x * blockDim.x)
+        atomicAdd((unsigned long long *)&Wt[(size_t)dst[e] * K + src[e]],
+                  (unsigned long long)nbytes[e]);
+}
+
+// row v: A[v][i] = sum over u < i of Wt[v][u], i = 0..K-1, in place (one block per row)
+__global__ __launch_bounds__(256) void row_prefix_kernel(int64_t *__restrict__ Wt, int K)
+{
+    __shared__ int64_t part[256];
+    const int t = threadIdx.x;
+    int64_t *row = Wt + (size_t)blockIdx.x * K;
+    const int per = (K + 255) / 256;
+    const int lo = min(K, t * per), hi = min(K, lo + per);
+    int64_t s = 0;
+    for (int x = lo; x < hi; ++x) s += row[x];
+    part[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const int64_t o = (t >= off) ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    int64_t run = part[t] - s;
+    for (int x = lo; x < hi; ++x) {
+        const int64_t w = row[x];
+        row[x] = run;
+        run += w;
+    }
+}
+
+// Column i: Ct[n][i] = sum over v = i..n of A[v][i] for n >= i (entries with n < i are not
+// used).  Three passes over chunks of CL_TILE rows: chunk sums, their prefix, the running sum.
+__global__ __launch_bounds__(64) void col_chunk_sum_kernel(const int64_t *__restrict__ A, int K,
+                                                           int64_t *__restrict__ chunk)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int r0 = blockIdx.y * CL_TILE;
+    if (i >= K) return;
+    int64_t s = 0;
+    const int r1 = min(K, r0 + CL_TILE);
+    for (int v = max(r0, i); v < r1; ++v) s += A[(size_t)v * K + i];
+    chunk[(size_t)blockIdx.y * K + i] = s;
+}
+
+__global__ void col_chunk_prefix_kernel(int64_t *__restrict__ chunk, int K, int n_chunks)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= K) return;
+    int64_t run = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t s = chunk[(size_t)c * K + i];
+        chunk[(size_t)c * K + i] = run;
+        run += s;
+    }
+}
+
+__global__ __launch_bounds__(64) void col_running_sum_kernel(int64_t *__restrict__ A, int K,
+                                                             const int64_t *__restrict__ chunk)
+{
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const int r0 = blockIdx.y * CL_TILE;
+    if (i >= K) return;
+    int64_t run = chunk[(size_t)blockIdx.y * K + i];
+    const int r1 = min(K, r0 + CL_TILE);
+    for (int v = max(r0, i); v < r1; ++v) {
+        run += A[(size_t)v * K + i];
+        A[(size_t)v * K + i] = run;
+    }
+}
+
+// G(., 0): only the empty prefix is finite
+__global__ void cluster_init_kernel(int64_t *__restrict__ G, int64_t *__restrict__ V, int K)
+{
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x <= K; x += gridDim.x * blockDim.x) {
+        G[x] = (x == 0) ? 0 : INF_I64;
+        V[x] = 0;
+    }
+}
+
+struct Lex {                    // (G, V, i): smaller is better, component by component
+    int64_t g, v;
+    int i;
+};
+__device__ __forceinline__ bool lex_less(const Lex &a, const Lex &b)
+{
+    return a.g < b.g || (a.g == b.g && (a.v < b.v || (a.v == b.v && a.i < b.i)));
+}
+__device__ __forceinline__ Lex lex_shfl_xor(const Lex &a, int m)
+{
+    Lex o;
+    o.g = i64_from(__shfl_xor(lo32(a.g), m, 64), __shfl_xor(hi32(a.g), m, 64));
+    o.v = i64_from(__shfl_xor(lo32(a.v), m, 64), __shfl_xor(hi32(a.v), m, 64));
+    o.i = __shfl_xor(a.i, m, 64);
+    return o;
+}
+
+// One layer count r: Gn[n], Vn[n], arg[n] for n = 1..K from Gp, Vp (r - 1).  One wave per n.
+__global__ __launch_bounds__(256) void cluster_layer_kernel(
+    const int64_t *__restrict__ Ct, const int64_t *__restrict__ pf, int K, int64_t cap,
+    const int64_t *__restrict__ Gp, const int64_t *__restrict__ Vp, int64_t *__restrict__ Gn,
+    int64_t *__restrict__ Vn, int32_t *__restrict__ arg)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6) + 1;          // prefix length, 1-based
+    if (n > K) return;                                              // whole wave
+    // smallest i (1-based) with pf[n] - pf[i-1] <= cap: bisection on the non-decreasing pf
+    const int64_t need = pf[n] - cap;                               // pf[i-1] >= need
+    int lo = 0, hi = n;                                             // answer index x = i-1 in [0, n]
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (pf[mid] >= need) hi = mid; else lo = mid + 1;
+    }
+    const int i_min = lo + 1;                                       // may be n + 1: nothing fits
+    Lex best{INF_I64, 0, 0};
+    const int64_t *row = Ct + (size_t)(n - 1) * K;                  // Ct[n-1][i-1] = C(i, n)
+    for (int i = i_min + lane; i <= n; i += WAVE) {
+        const int64_t gp = Gp[i - 1];
+        if (gp == INF_I64) continue;
+        const int64_t c = row[i - 1];
+        const int64_t f = pf[n] - pf[i - 1];
+        const Lex cur{gp > c ? gp : c, Vp[i - 1] + f * f, i};
+        if (lex_less(cur, best)) best = cur;
+    }
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) {
+        const Lex o = lex_shfl_xor(best, m);
+        if (lex_less(o, best)) best = o;
+    }
+    if (best.g == INF_I64) { best.v = 0; best.i = 0; }
+    Gn[n] = best.g;                                                 // all lanes, same value
+    Vn[n] = best.v;
+    arg[n] = best.i;
+    if (lane == 0 && n == 1) { Gn[0] = INF_I64; Vn[0] = 0; arg[0] = 0; }   // G(0, r > 0)
+}
+
+// out[0] = G(K, L), out[1] = V(K, L); first_op[0..L] by walking arg back (one thread)
+__global__ void cluster_walk_kernel(const int64_t *__restrict__ G, const int64_t *__restrict__ V,
+                                    const int32_t *__restrict__ arg, int K, int L,
+                                    int64_t *__restrict__ out, int32_t *__restrict__ first_op)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const int64_t g = G[K];
+    out[0] = g;
+    out[1] = g == INF_I64 ? 0 : V[K];
+    if (g == INF_I64) {
+        for (int r = 0; r <= L; ++r) first_op[r] = -1;
+        return;
+    }
+    int n = K;
+    first_op[L] = K;
+    for (int r = L; r >= 1; --r) {
+        const int i = arg[(size_t)(r - 1) * (K + 1) + n];
+        first_op[r - 1] = i - 1;
+        n = i - 1;
+    }
+}
+
+hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *src,
+                          const int32_t *dst, const int64_t *nbytes, int E, int K, int L,
+                          int64_t cap, int64_t *Ct, int64_t *chunk, int64_t *pf, int64_t *GV,
+                          int32_t *arg, int64_t *out, int32_t *first_op)
+{
+    hipLaunchKernelGGL(flop_prefix_kernel, dim3(1), dim3(1024), 0, st, flop, K, pf);
+    const long long kk = (long long)K * K;
+    hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)std::min<long long>((kk + 255) / 256, 4096)),
+                       dim3(256), 0, st, Ct, kk);
+    if (E > 0)
+        hipLaunchKernelGGL(edges_to_matrix_kernel, dim3((E + 255) / 256), dim3(256), 0, st, src, dst,
+                           nbytes, E, K, Ct);
+    hipLaunchKernelGGL(row_prefix_kernel, dim3(K), dim3(256), 0, st, Ct, K);
+    const int n_chunks = (K + CL_TILE - 1) / CL_TILE;
+    const dim3 cgrid((K + 63) / 64, n_chunks);
+    hipLaunchKernelGGL(col_chunk_sum_kernel, cgrid, dim3(64), 0, st, Ct, K, chunk);
+    hipLaunchKernelGGL(col_chunk_prefix_kernel, dim3((K + 255) / 256), dim3(256), 0, st, chunk, K,
+                       n_chunks);
+    hipLaunchKernelGGL(col_running_sum_kernel, cgrid, dim3(64), 0, st, Ct, K, chunk);
+    // GV: G and V rows of two consecutive layer counts, [2][2][K + 1]
+    int64_t *G[2] = {GV, GV + 2 * (size_t)(K + 1)};
+    int64_t *V[2] = {GV + (K + 1), GV + 3 * (size_t)(K + 1)};
+    hipLaunchKernelGGL(cluster_init_kernel, dim3((K + 256) / 256), dim3(256), 0, st, G[0], V[0], K);
+    for (int r = 1; r <= L; ++r) {
+        const int p = (r - 1) & 1, c = r & 1;
+        hipLaunchKernelGGL(cluster_layer_kernel, dim3((K + 3) / 4), dim3(256), 0, st, Ct, pf, K, cap,
+                           G[p], V[p], G[c], V[c], arg + (size_t)(r - 1) * (K + 1));
+    }
+    hipLaunchKernelGGL(cluster_walk_kernel, dim3(1), dim3(WAVE), 0, st, G[L & 1], V[L & 1], arg, K, L,
+                       out, first_op);
+    return hipGetLastError();
+}
+
+size_t cluster_chunk_rows(int K) { return (size_t)((K + CL_TILE - 1) / CL_TILE); }
+
+}  // namespace alpa

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "alpa_dp.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(alpa_dp_[a-z_A-Z]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(alpa_(?:dp|cluster)_[a-z_A-Z]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -77,3 +77,27 @@ def test_null_handle_is_rejected():
     assert L.alpa_dp_best(None, None) == -1
     assert L.alpa_dp_set_B(None, 3) == -1
     L.alpa_dp_destroy(None)
+
+
+def test_clustering_rejects_bad_arguments_on_the_host():
+    flop = np.asarray([3, 1, 2, 2], np.int32)
+    src = np.asarray([0, 1, 2], np.int32)
+    dst = np.asarray([1, 2, 3], np.int32)
+    nb = np.asarray([5, 5, 5], np.int64)
+
+    def rc(flop=flop, src=src, dst=dst, nb=nb, E=3, K=4, L=2, delta=500000):
+        L_ = B.load()
+        out = (ctypes.c_int64(), ctypes.c_int64(), (ctypes.c_int32 * (max(L, 0) + 1))())
+        return L_.alpa_cluster_layers(flop.ctypes.data if flop is not None else None, K,
+                                      src.ctypes.data, dst.ctypes.data, nb.ctypes.data, E, L, delta,
+                                      ctypes.byref(out[0]), ctypes.byref(out[1]), out[2], None)
+
+    assert rc(flop=None) == -1
+    assert rc(K=0) == -1 and rc(K=B.CLUSTER_MAX_OPS + 1) == -1
+    assert rc(L=0) == -1 and rc(delta=-1) == -1 and rc(E=-1) == -1
+    assert rc(flop=np.asarray([3, -1, 2, 2], np.int32)) == -1
+    assert rc(src=np.asarray([0, 2, 2], np.int32)) == -1            # src >= dst
+    assert rc(dst=np.asarray([1, 2, 4], np.int32)) == -1            # dst >= K
+    assert rc(nb=np.asarray([5, -5, 5], np.int64)) == -1
+    assert rc(flop=np.asarray([2**30, 2**30, 0, 0], np.int32)) == -2
+    assert rc(nb=np.asarray([2**61, 2**61, 5], np.int64)) == -2
