@@ -119,6 +119,11 @@ def main():
     create_prof_s = time.perf_counter() - t0
     B.alpa_dp_destroy(h2)
 
+    # operator clustering (Eq. 6), outside the timed region: 80 transformer-like blocks, 64 layers
+    og = W.make_op_graph(80, 80)
+    B.alpa_cluster_layers(og.flop, og.src, og.dst, og.nbytes, 64, 500000)
+    cl = B.alpa_cluster_layers(og.flop, og.src, og.dst, og.nbytes, 64, 500000)
+
     # check against the stored oracle results for this workload, if present
     verified = None
     gpath = os.path.join(ROOT, "tests", "golden", f"workload_{args.workload}.json")
@@ -157,6 +162,7 @@ def main():
                   "ms_recurrence_avg": rec_avg, "ms_epilogue_avg": float(np.mean(epi_ms)),
                   "ms_sweep_16_B_values_blocking_call": sweep_ms,
                   "sweep_T_star_by_B": {str(b): pl["T_star"] for b, pl in zip(sweep_B, sweep_plans)},
+                  "cluster_K%d_L64_device_ms" % og.K: cl["ms"], "cluster_comm_bytes": cl["comm"],
                   "create_s": create_s, "create_from_profiles_6_options_s": create_prof_s, "T_star": plan["T_star"], "t_max": plan["t_max"],
                   "num_stages": plan["num_stages"], "matches_stored_oracle": verified,
                   "paper_context": "Stage Construction DP 1.65 s (Table 5; GPT-39B, 64 V100 "

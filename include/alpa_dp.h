@@ -123,6 +123,16 @@ int alpa_dp_create_from_profiles(alpa_dp_t **out, const int32_t *t_l,
                                  int K, int N, int M, int B,
                                  const alpa_shape_t *shapes, int num_shapes);
 
+/*
+ * "Equal layer" variant of the ablation study (Sec. 8.3): restricts the handle, for good, to
+ * plans whose stages all have the same number of layers.  With s stages from first layer k
+ * to the last one that number is (K - k) / s, so table entry (s, k, i) is kept iff s divides
+ * K - k and i - k + 1 == (K - k) / s; every other entry becomes +infinity.  The candidate
+ * count (alpa_dp_count_candidates) changes with it and the running best of alpa_dp_best is
+ * reset.  Blocking.
+ */
+int alpa_dp_restrict_equal_layers(alpa_dp_t *h);
+
 /* Copies the handle's table, C order [s-1][k][i][q] (K x K x K x num_shapes int32), to
  * the HOST array out_table.  Blocking. */
 int alpa_dp_get_table(alpa_dp_t *h, int32_t *out_table);
@@ -254,6 +264,24 @@ int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
                         const int32_t *edge_dst, const int64_t *edge_bytes, int num_edges,
                         int L, int delta_ppm, int64_t *out_comm, int64_t *out_sumsq,
                         int32_t *out_first_op, float *out_ms);
+
+/*
+ * Physical placement of the submeshes a plan chose (Sec. 5.2: devices go to larger submeshes
+ * first, then to smaller ones, and neighbouring stages of one shape are put next to each other;
+ * Appendix A shows the shapes always cover the mesh, and the construction follows its proof).
+ * Host-only (no device work), stateless.
+ *
+ *   stage_shapes  HOST array of num_stages (n, m) in pipeline order (shapes[plan.shape_idx[p]]),
+ *                 each from the family of Sec. 5.2, device counts adding up to N * M.
+ *   out_row/col   HOST int32 [num_stages]: stage p owns rows [row, row + n) x columns
+ *                 [col, col + m) of the N x M mesh (device id = row * M + col).
+ * Order: device count descending, equal counts in pipeline order; positions in row-major order.
+ *
+ * Errors: EINVAL (null pointer, sizes out of range, M not a power of two, a shape outside the
+ * family, device counts not adding up).
+ */
+int alpa_place_submeshes(int N, int M, const alpa_shape_t *stage_shapes, int num_stages,
+                         int32_t *out_row, int32_t *out_col);
 
 #ifdef __cplusplus
 }

@@ -104,6 +104,21 @@ def build_table(t_l, mem_stage, mem_act, mem_device: int) -> np.ndarray:
     return table
 
 
+def equal_layer_table(table) -> np.ndarray:
+    """The "Equal layer" variant of the ablation study (Sec. 8.3: the DP restricted to the same
+    number of layers for all stages), stated on the table: with s stages from first layer k to
+    the last, each has (K - k) / s layers, so only such entries stay finite.  Plain loops."""
+    table = np.array(table, dtype=np.int32, copy=True)
+    K = table.shape[0]
+    for s in range(1, K + 1):
+        for k in range(K):
+            for i in range(K):
+                rest = K - k
+                if rest % s != 0 or (i - k + 1) * s != rest:
+                    table[s - 1, k, i, :] = INF32
+    return table
+
+
 _lib_cluster = None
 
 

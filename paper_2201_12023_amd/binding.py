@@ -25,11 +25,12 @@ ALPA_DP_PRUNE = 1
 ALPA_DP_GENERIC = 2
 ALPA_DP_COUNT_WORK = 4
 
-SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_count_candidates",
+SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table",
+           "alpa_dp_restrict_equal_layers", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_count_candidates",
            "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
            "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
-           "alpa_dp_last_error", "alpa_cluster_layers"]
+           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_place_submeshes"]
 
 
 class alpa_shape_t(ctypes.Structure):
@@ -80,6 +81,7 @@ def load():
                                                ctypes.c_int, ctypes.c_int,
                                                ctypes.POINTER(alpa_shape_t), ctypes.c_int]
     L.alpa_dp_get_table.argtypes = [vp, vp]
+    L.alpa_dp_restrict_equal_layers.argtypes = [vp]
     L.alpa_dp_set_stream.argtypes = [vp, vp]
     L.alpa_dp_set_B.argtypes = [vp, ctypes.c_int]
     L.alpa_dp_count_candidates.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]
@@ -93,6 +95,8 @@ def load():
     L.alpa_cluster_layers.argtypes = [vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, i64p, i64p, vp,
                                       ctypes.POINTER(ctypes.c_float)]
+    L.alpa_place_submeshes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(alpa_shape_t),
+                                       ctypes.c_int, vp, vp]
     L.alpa_dp_destroy.argtypes = [vp]
     L.alpa_dp_destroy.restype = None
     L.alpa_dp_last_error.restype = ctypes.c_char_p
@@ -142,6 +146,10 @@ def alpa_dp_get_table(h, K, S) -> np.ndarray:
     out = np.empty((K, K, K, S), dtype=np.int32)
     _check(load().alpa_dp_get_table(h, out.ctypes.data))
     return out
+
+
+def alpa_dp_restrict_equal_layers(h):
+    _check(load().alpa_dp_restrict_equal_layers(h))
 
 
 def alpa_dp_set_stream(h, stream):
@@ -264,3 +272,14 @@ def alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm):
     feasible = comm.value != INF_I64
     return {"comm": int(comm.value), "sumsq": int(sumsq.value),
             "first_op": [int(x) for x in first] if feasible else [], "ms": float(ms.value)}
+
+
+def alpa_place_submeshes(N, M, stage_shapes):
+    """stage_shapes: (n, m) per stage in pipeline order.  Returns [(row, col)] per stage."""
+    shp = np.ascontiguousarray(stage_shapes, dtype=np.int32).reshape(-1, 2)
+    n = shp.shape[0]
+    arr = (alpa_shape_t * max(n, 1))(*[alpa_shape_t(int(a), int(b)) for a, b in shp])
+    row = np.zeros(max(n, 1), np.int32)
+    col = np.zeros(max(n, 1), np.int32)
+    _check(load().alpa_place_submeshes(int(N), int(M), arr, n, row.ctypes.data, col.ctypes.data))
+    return [(int(r), int(c)) for r, c in zip(row[:n], col[:n])]

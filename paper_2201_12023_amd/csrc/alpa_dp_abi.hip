@@ -371,6 +371,32 @@ extern "C" int alpa_dp_create_from_profiles(alpa_dp_t **out, const int32_t *t_l,
     });
 }
 
+extern "C" int alpa_dp_restrict_equal_layers(alpa_dp_t *h)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    const int K = h->p.K, S = h->p.S;
+    HIPCHK(launch_equal_layer_mask(h->stream, h->d_table, K, S));
+    if (h->fast_ok) {
+        HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
+        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
+    }
+    // the candidate list changes with the table; the running best belonged to the old one
+    int rc = queue_table_candidates(h);
+    if (rc) return rc;
+    uint32_t nd = 0;
+    HIPCHK(hipMemcpyAsync(&nd, h->d_ncount, 4, hipMemcpyDeviceToHost, h->stream));
+    HIPCHK(launch_init_best_plan(h->stream, h->d_best_plan));
+    HIPCHK(hipStreamSynchronize(h->stream));
+    h->n_distinct = (int)nd;
+    h->any_solve = false;
+    return ALPA_DP_OK;
+}
+
 extern "C" int alpa_dp_get_table(alpa_dp_t *h, int32_t *out_table)
 {
     if (!h || !out_table) return fail(ALPA_DP_EINVAL, "null argument");

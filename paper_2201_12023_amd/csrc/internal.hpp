@@ -133,6 +133,8 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
                               const int64_t *mem_act, int K, int S, int O, int64_t mem_device,
                               int32_t *table, int32_t *max_finite);
 
+hipError_t launch_equal_layer_mask(hipStream_t st, int32_t *table, int K, int S);
+
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
                               int32_t *recs);
 size_t fast_table_ints(int K, int S);    // size of the column-record array, padding included

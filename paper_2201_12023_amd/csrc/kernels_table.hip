@@ -72,6 +72,33 @@ __global__ __launch_bounds__(TABLE_BLOCK) void build_table_kernel(
     if ((tid & (WAVE - 1)) == 0 && mx >= 0) atomicMax(max_finite, mx);
 }
 
+// "Equal layer" variant of the ablation study (Sec. 8.3): every stage of a plan has the same
+// number of layers.  With s stages from first layer k to the end that number is (K - k) / s, so
+// the restriction is a mask on the table: entry (s, k, i) stays iff s divides K - k and the
+// stage k..i has exactly (K - k) / s layers.
+__global__ void equal_layer_mask_kernel(int32_t *__restrict__ table, int K, int S)
+{
+    const long long total = (long long)K * K * K * S;
+    for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        long long r = e / S;
+        const int i = (int)(r % K); r /= K;
+        const int k = (int)(r % K);
+        const int s = (int)(r / K) + 1;
+        const int rest = K - k;
+        const bool keep = rest % s == 0 && i - k + 1 == rest / s;
+        if (!keep) table[e] = INF_I32;
+    }
+}
+
+hipError_t launch_equal_layer_mask(hipStream_t st, int32_t *table, int K, int S)
+{
+    const long long total = (long long)K * K * K * S;
+    int grid = (int)std::min<long long>((total + 255) / 256, 8192);
+    hipLaunchKernelGGL(equal_layer_mask_kernel, dim3(grid), dim3(256), 0, st, table, K, S);
+    return hipGetLastError();
+}
+
 __global__ void set_i32_kernel(int32_t *p, int32_t v)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "alpa_dp.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(alpa_(?:dp|cluster)_[a-z_A-Z]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(alpa_(?:dp|cluster|place)_[a-z_A-Z]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
