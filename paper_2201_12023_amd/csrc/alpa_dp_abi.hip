@@ -48,7 +48,7 @@ struct alpa_dp {
     int n_cu = 0;
     bool fast_ok = false;
     int KP = 0;
-    int fast_grid_max[3] = {0, 0, 0}, generic_grid_max = 0;   // [nc] for nc = 1, 2
+    int fast_grid_max[5] = {0, 0, 0, 0, 0}, generic_grid_max = 0;   // [nc] for nc = 1..4
 
     int32_t *d_table = nullptr, *d_sizes = nullptr, *d_recs = nullptr;
     PrepBuffers pb{};
@@ -244,7 +244,7 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
         HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
         HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
         HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
-        for (int nc = 1; nc <= 2; ++nc) {
+        for (int nc = 1; nc <= 4; ++nc) {
             int per_cu = fast_kernel_blocks_per_cu(K, nc);
             if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
             if (const char *e = getenv("ALPA_DP_WG_PER_CU")) {   // tuning aid
@@ -492,7 +492,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             // two candidates per workgroup share every scalar load; worth it once there are
             // enough candidates to fill the device twice over that way
             int nc = (bound >= 4 * h->fast_grid_max[2]) ? 2 : 1;
-            if (const char *e = getenv("ALPA_DP_NC")) nc = atoi(e) == 2 ? 2 : 1;   // tuning aid
+            if (const char *e = getenv("ALPA_DP_NC")) nc = std::min(4, std::max(1, atoi(e)));   // tuning aid
             const int grid = std::max(1, std::min((bound + nc - 1) / nc, h->fast_grid_max[nc]));
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,

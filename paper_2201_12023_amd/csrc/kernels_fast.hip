@@ -6,7 +6,7 @@
 // ceil(K / 16) waves along that axis and wave w owns half-blocks w ("A") and 2*NWK-1-w
 // ("B"): the triangular work (a column with last layer i only touches first layers <= i)
 // is then the same for every wave.  The 16 accumulators F(s, k, .) of a wave live in VGPRs;
-// with WI > 1 the (last layer) columns are dealt round-robin over WI wave groups and the
+// with WI > 1 the submesh shapes q are dealt round-robin over WI wave groups and the
 // partial minima are merged through LDS.  The previous layer F(s-1, ., .) lives in LDS, one
 // row of 64 lanes per first layer.  For a fixed (last layer i, shape q) the operand
 // F(s-1, i+1, d - a_q) is one lane-shifted LDS row read, reused for all first layers of the
@@ -26,6 +26,8 @@
 // The array is padded by a few records so that the one-column-ahead loads may run past the
 // last column.
 #include "internal.hpp"
+
+#include <type_traits>
 
 namespace alpa {
 
@@ -128,6 +130,44 @@ __device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)
     }
 }
 
+// Two candidates in one pass.  Where every device count a shape can still serve at this layer
+// lies in one window of 32 (d - 1 in [base, base + 32)), lanes 0..31 work for candidate 0 and
+// lanes 32..63 for candidate 1, both on that window: the scalar t_intra values are the same
+// for both, so one add + min per first layer serves the two of them.  GP is the packed operand
+// (lane l: F(s-1, i+1, d - a_q) of candidate l / 32), accP the packed accumulators.  If every
+// finite entry passes both candidates one update does it; otherwise each candidate gets its
+// own filtered update with the other half's operand set to infinity.
+template <bool COUNT>
+__device__ __forceinline__ void relax8p(int32_t (&accP)[16], int off, int32_t (&t)[8], int32_t mn,
+                                        int32_t mx, int32_t GP, const int32_t (&c)[2], bool half1,
+                                        unsigned &n_blocks)
+{
+    if (mn <= c[1]) {                         // else nothing passes even the larger candidate
+        const bool both = mx <= c[0];
+        if (mx > c[1]) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[1]) ? t[u] : DEV_INF;
+        }
+        const int32_t G1 = (both || half1) ? GP : DEV_INF;
+        if (COUNT) ++n_blocks;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) accP[off + u] = min(accP[off + u], t[u] + G1);
+        if (!both) {
+            asm volatile("" : "+s"(t[0]), "+s"(t[1]), "+s"(t[2]), "+s"(t[3]), "+s"(t[4]),
+                              "+s"(t[5]), "+s"(t[6]), "+s"(t[7]), "+v"(accP[off + 0]),
+                              "+v"(accP[off + 1]), "+v"(accP[off + 2]), "+v"(accP[off + 3]),
+                              "+v"(accP[off + 4]), "+v"(accP[off + 5]), "+v"(accP[off + 6]),
+                              "+v"(accP[off + 7]));
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[0]) ? t[u] : DEV_INF;
+            const int32_t G0 = half1 ? DEV_INF : GP;
+            if (COUNT) ++n_blocks;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) accP[off + u] = min(accP[off + u], t[u] + G0);
+        }
+    }
+}
+
 // Lower-index evidence for the pruning rule (see recurrence_generic_kernel).
 __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, int32_t c, int B,
                                               int lane)
@@ -140,7 +180,7 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
     return m != INF_I64 && (int64_t)B * (int64_t)c >= m;
 }
 
-// NWK = waves along the first-layer axis (= ceil(K / 16)); WI = waves along the column
+// NWK = waves along the first-layer axis (= ceil(K / 16)); WI = wave groups along the shape
 // axis; NC = candidates evaluated together by one workgroup (they share every scalar load);
 // DUMP = also store every layer to F_all (plan recovery, NC = 1); COUNT = tally executed
 // half-blocks.  Fmin / Sbest have a spare slot at index dummy_idx for results nobody owns.
@@ -155,7 +195,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
-    constexpr int ROWS = KP + 6 * WI;                  // LDS rows per F layer (+ read-ahead slack)
+    constexpr int ROWS = KP + 6;                       // LDS rows per F layer (+ read-ahead slack)
     extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
     __shared__ int32_t sh_tk[NT];
     __shared__ int32_t sh_skip[NWK * WI];
@@ -172,6 +212,13 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     const cptr_t sizes = (cptr_t)sizes_g;
     int32_t *Fprev = lds;
     int32_t *Fnext = lds + NC * ROWS * WAVE;
+    // candidate packing (two candidates, one pass): lane l works for candidate l / 32 on
+    // device count d - 1 = pk_base + l % 32
+    constexpr bool PACK = NC == 2 && WI == 1 && !DUMP;
+    const int pk_base = max(0, D - 32);
+    const int pk_dl = pk_base + (lane & 31);
+    const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
+    const bool half1 = lane >= 32;
     const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
     const int n_groups = (n + NC - 1) / NC;
     unsigned long long n_blocks_total = 0;
@@ -236,20 +283,24 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
             for (int e = 0; e < NC; ++e)
 #pragma unroll
                 for (int u = 0; u < 16; ++u) acc[e][u] = DEV_INF;
+            int32_t accP[16];                          // packed passes (PACK only)
+#pragma unroll
+            for (int u = 0; u < 16; ++u) accP[u] = DEV_INF;
+            int32_t c2[2] = {c[0], c[NC - 1]};
             const int i_lo = (s == 1) ? K - 1 : 0;     // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
-            const int i0 = max(i_lo, rowA) + wi;       // columns that reach half-block A
+            const int i0 = max(i_lo, rowA);            // columns that reach half-block A
             if (WI > 1) {
                 for (int x = tid; x < NC * ROWS * WAVE; x += NT) Fnext[x] = DEV_INF;
             }
-            for (int q = 0; q < S; ++q) {
+            for (int q = wi; q < S; q += WI) {          // wave group wi takes every WI-th shape
                 const int a = sizes[q];
                 if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
                 if (i0 > i_hi) continue;
-                constexpr int STEP = REC * WI;
+                constexpr int STEP = REC;
                 const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
                 cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
-                const int ncol = (i_hi - i0) / WI + 1;         // columns of this wave
+                const int ncol = i_hi - i0 + 1;                // columns of this wave
                 HalfColumn hA, hB;
                 int32_t G[NC];
                 if (s == 1) {
@@ -257,7 +308,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
 #pragma unroll
                     for (int e = 0; e < NC; ++e) G[e] = (lane + 1 == a) ? 0 : DEV_INF;
                     int i = i0;
-                    for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, i += WI) {
+                    for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, ++i) {
                         load_half(hA, pA);
                         load_half(hB, pB);
                         relax8<NC, COUNT>(acc, 0, hA.t, mnA(hA), hA.mx, G, c, n_blocks);
@@ -265,112 +316,145 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                     }
                     continue;
                 }
-                // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
-                // their LDS rows; while one batch is computed the loads of the next are in
-                // flight, so every wait is covered by a whole batch of updates.  Where only
-                // half-block A is reached (last layer < rowB) a batch is the A halves of two
-                // columns, afterwards it is the A and B halves of one column.  Loads past
-                // the last column land in the padding and are dropped.
-                const bool live = lane >= a;           // d - a_q >= 1
-                const int32_t *frow = Fprev + (live ? lane - a : 0) + (i0 + 1) * WAVE;   // row i+1
-                struct Batch { HalfColumn X, Y; int32_t fX[NC], fY[NC]; } b0, b1;
-                auto rows = [&](int32_t (&dst)[NC], int col) {     // col: columns ahead of frow
-#pragma unroll
-                    for (int e = 0; e < NC; ++e) dst[e] = frow[(e * ROWS + col * WI) * WAVE];
-                };
-                auto operands = [&](const int32_t (&src)[NC]) {
-#pragma unroll
-                    for (int e = 0; e < NC; ++e) G[e] = live ? src[e] : DEV_INF;
-                };
-                auto settle_batch = [&](const Batch &b) {
-                    settle(b.X, b.fX[0]);
-                    settle(b.Y, b.fY[0]);
-                };
-                // --- columns that only reach half-block A: slots = columns i and i + WI
-                auto load_AA = [&](Batch &b, int col) {
-                    rows(b.fX, col);
-                    rows(b.fY, col + 1);
-                    load_half(b.X, pA + (size_t)col * STEP);
-                    load_half(b.Y, pA + (size_t)(col + 1) * STEP);
-                    fence_loads();
-                };
-                auto compute_AA = [&](Batch &b) {
-                    operands(b.fX);
-                    relax8<NC, COUNT>(acc, 0, b.X.t, mnA(b.X), b.X.mx, G, c, n_blocks);
-                    operands(b.fY);
-                    relax8<NC, COUNT>(acc, 0, b.Y.t, mnA(b.Y), b.Y.mx, G, c, n_blocks);
-                };
-                const int n1 = max(0, min((rowB - i0 + WI - 1) / WI, ncol));
-                int left = n1;
-                if (DUMP && !needA) {                  // nothing to do in this phase
-                    left = 0;
-                    pA += (size_t)n1 * STEP;
-                    frow += n1 * WI * WAVE;
-                }
-                if (left >= 2) {
-                    load_AA(b0, 0);
-                    for (; left >= 4; left -= 4) {
-                        settle_batch(b0);
-                        load_AA(b1, 2);
-                        compute_AA(b0);
-                        settle_batch(b1);
-                        load_AA(b0, 4);
-                        compute_AA(b1);
-                        pA += 4 * STEP;
-                        frow += 4 * WI * WAVE;
+                auto columns = [&](auto PK) {
+                    // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
+                    // their LDS rows; while one batch is computed the loads of the next are in
+                    // flight, so every wait is covered by a whole batch of updates.  Where only
+                    // half-block A is reached (last layer < rowB) a batch is the A halves of two
+                    // columns, afterwards it is the A and B halves of one column.  Loads past
+                    // the last column land in the padding and are dropped.
+                    // P: the two candidates share each pass (see relax8p); one LDS row per column
+                    constexpr bool P = decltype(PK)::value;
+                    constexpr int NF = P ? 1 : NC;
+                    const int dl = P ? pk_dl : lane;       // d - 1 served by this lane
+                    const bool live = dl >= a;             // d - a_q >= 1
+                    const int32_t *frow = Fprev + (P ? pk_cand_off : 0) + (live ? dl - a : 0) +
+                                          (i0 + 1) * WAVE;                         // row i+1
+                    struct Batch { HalfColumn X, Y; int32_t fX[NF], fY[NF]; } b0, b1;
+                    auto rows = [&](int32_t (&dst)[NF], int col) {     // col: columns ahead of frow
+    #pragma unroll
+                        for (int e = 0; e < NF; ++e) dst[e] = frow[(e * ROWS + col) * WAVE];
+                    };
+                    auto operands = [&](const int32_t (&src)[NF]) {
+    #pragma unroll
+                        for (int e = 0; e < NF; ++e) G[e] = live ? src[e] : DEV_INF;
+                    };
+                    auto relax = [&](int off, HalfColumn &h, int32_t mn) {
+                        if constexpr (P)
+                            relax8p<COUNT>(accP, off, h.t, mn, h.mx, G[0], c2, half1, n_blocks);
+                        else
+                            relax8<NC, COUNT>(acc, off, h.t, mn, h.mx, G, c, n_blocks);
+                    };
+                    auto settle_batch = [&](const Batch &b) {
+                        settle(b.X, b.fX[0]);
+                        settle(b.Y, b.fY[0]);
+                    };
+                    // --- columns that only reach half-block A: slots = columns i and i + 1
+                    auto load_AA = [&](Batch &b, int col) {
+                        rows(b.fX, col);
+                        rows(b.fY, col + 1);
+                        load_half(b.X, pA + (size_t)col * STEP);
+                        load_half(b.Y, pA + (size_t)(col + 1) * STEP);
+                        fence_loads();
+                    };
+                    auto compute_AA = [&](Batch &b) {
+                        operands(b.fX);
+                        relax(0, b.X, mnA(b.X));
+                        operands(b.fY);
+                        relax(0, b.Y, mnA(b.Y));
+                    };
+                    const int n1 = max(0, min(rowB - i0, ncol));
+                    int left = n1;
+                    if (DUMP && !needA) {                  // nothing to do in this phase
+                        left = 0;
+                        pA += (size_t)n1 * STEP;
+                        frow += n1 * WAVE;
                     }
                     if (left >= 2) {
-                        settle_batch(b0);
-                        compute_AA(b0);
-                        pA += 2 * STEP;
-                        frow += 2 * WI * WAVE;
-                        left -= 2;
-                    }
-                }
-                if (left == 1) {
-                    rows(b0.fX, 0);
-                    load_half(b0.X, pA);
-                    operands(b0.fX);
-                    relax8<NC, COUNT>(acc, 0, b0.X.t, mnA(b0.X), b0.X.mx, G, c, n_blocks);
-                    pA += STEP;
-                    frow += WI * WAVE;
-                }
-                // --- columns that reach both half-blocks: slots = halves A and B of a column
-                pB += (size_t)n1 * STEP;
-                auto load_AB = [&](Batch &b, int col) {
-                    rows(b.fX, col);
-                    load_half(b.X, pA + (size_t)col * STEP);
-                    load_half(b.Y, pB + (size_t)col * STEP);
-                    fence_loads();
-                };
-                auto compute_AB = [&](Batch &b) {
-                    operands(b.fX);
-                    relax8<NC, COUNT>(acc, 0, b.X.t, mnA(b.X), b.X.mx, G, c, n_blocks);
-                    relax8<NC, COUNT>(acc, 8, b.Y.t, mnB(b.Y), b.Y.mx, G, c, n_blocks);
-                };
-                auto settle_AB = [&](const Batch &b) {
-                    settle(b.X, b.fX[0]);
-                    settle(b.Y);
-                };
-                left = ncol - n1;
-                if (left >= 1) {
-                    load_AB(b0, 0);
-                    for (; left >= 2; left -= 2) {
-                        settle_AB(b0);
-                        load_AB(b1, 1);
-                        compute_AB(b0);
-                        settle_AB(b1);
-                        load_AB(b0, 2);
-                        compute_AB(b1);
-                        pA += 2 * STEP;
-                        pB += 2 * STEP;
-                        frow += 2 * WI * WAVE;
+                        load_AA(b0, 0);
+                        for (; left >= 4; left -= 4) {
+                            settle_batch(b0);
+                            load_AA(b1, 2);
+                            compute_AA(b0);
+                            settle_batch(b1);
+                            load_AA(b0, 4);
+                            compute_AA(b1);
+                            pA += 4 * STEP;
+                            frow += 4 * WAVE;
+                        }
+                        if (left >= 2) {
+                            settle_batch(b0);
+                            compute_AA(b0);
+                            pA += 2 * STEP;
+                            frow += 2 * WAVE;
+                            left -= 2;
+                        }
                     }
                     if (left == 1) {
-                        settle_AB(b0);
-                        compute_AB(b0);
+                        rows(b0.fX, 0);
+                        load_half(b0.X, pA);
+                        operands(b0.fX);
+                        relax(0, b0.X, mnA(b0.X));
+                        pA += STEP;
+                        frow += WAVE;
                     }
+                    // --- columns that reach both half-blocks: slots = halves A and B of a column
+                    pB += (size_t)n1 * STEP;
+                    auto load_AB = [&](Batch &b, int col) {
+                        rows(b.fX, col);
+                        load_half(b.X, pA + (size_t)col * STEP);
+                        load_half(b.Y, pB + (size_t)col * STEP);
+                        fence_loads();
+                    };
+                    auto compute_AB = [&](Batch &b) {
+                        operands(b.fX);
+                        relax(0, b.X, mnA(b.X));
+                        relax(8, b.Y, mnB(b.Y));
+                    };
+                    auto settle_AB = [&](const Batch &b) {
+                        settle(b.X, b.fX[0]);
+                        settle(b.Y);
+                    };
+                    left = ncol - n1;
+                    if (left >= 1) {
+                        load_AB(b0, 0);
+                        for (; left >= 2; left -= 2) {
+                            settle_AB(b0);
+                            load_AB(b1, 1);
+                            compute_AB(b0);
+                            settle_AB(b1);
+                            load_AB(b0, 2);
+                            compute_AB(b1);
+                            pA += 2 * STEP;
+                            pB += 2 * STEP;
+                            frow += 2 * WAVE;
+                        }
+                        if (left == 1) {
+                            settle_AB(b0);
+                            compute_AB(b0);
+                        }
+                    }
+            
+                };
+                if constexpr (PACK) {
+                    // packed when every device count the shape can still serve is in the window
+                    if (a + s - 2 >= pk_base) columns(std::true_type{});
+                    else columns(std::false_type{});
+                } else {
+                    columns(std::false_type{});
                 }
+            }
+            if (PACK) {
+                // lane l (d - 1 = l) takes candidate e's packed result from lane 32 e + l - pk_base
+                const int rel = lane - pk_base;
+                const bool in_window = rel >= 0 && rel < 32;
+#pragma unroll
+                for (int e = 0; e < NC; ++e)
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const int32_t v = __shfl(accP[u], (32 * e + rel) & 63, 64);
+                        acc[e][u] = min(acc[e][u], in_window ? v : DEV_INF);
+                    }
             }
             __syncthreads();                           // every wave is done reading Fprev
             int32_t f1[NC];
@@ -460,18 +544,24 @@ size_t fast_table_ints(int K, int S)
     return ((size_t)K * S * K + 32) * (size_t)((KP / 8) * HB_INTS);     // 32 records of padding
 }
 
-constexpr int PLAN_WI = 4;       // column-axis waves of the single-candidate (plan) run
+constexpr int PLAN_WI = 4;       // shape-axis wave groups of the single-candidate (plan) run
 
 template <int NWK, int WI, int NC>
 static size_t fast_lds_bytes()
 {
-    return (size_t)NC * (NWK * 16 + 6 * WI) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
+    return (size_t)NC * (NWK * 16 + 6) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
 }
 
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
 static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
 {
     const size_t lds = fast_lds_bytes<NWK, WI, NC>();
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(
+            (const void *)recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>,
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>), dim3(grid),
                        dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
                        a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
@@ -485,15 +575,23 @@ static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc
     switch (mode) {
     case FAST_MODE_PLAN: return launch_one<NWK, PLAN_WI, 1, true, false>(st, a, grid);
     case FAST_MODE_COUNT:
-        return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
-                       : launch_one<NWK, 1, 1, false, true>(st, a, grid);
+        switch (nc) {
+        case 4: return launch_one<NWK, 1, 4, false, true>(st, a, grid);
+        case 3: return launch_one<NWK, 1, 3, false, true>(st, a, grid);
+        case 2: return launch_one<NWK, 1, 2, false, true>(st, a, grid);
+        default: return launch_one<NWK, 1, 1, false, true>(st, a, grid);
+        }
     default:
-        return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
-                       : launch_one<NWK, 1, 1, false, false>(st, a, grid);
+        switch (nc) {
+        case 4: return launch_one<NWK, 1, 4, false, false>(st, a, grid);
+        case 3: return launch_one<NWK, 1, 3, false, false>(st, a, grid);
+        case 2: return launch_one<NWK, 1, 2, false, false>(st, a, grid);
+        default: return launch_one<NWK, 1, 1, false, false>(st, a, grid);
+        }
     }
 }
 
-// nc = candidates per workgroup (1 or 2); grid = persistent workgroups
+// nc = candidates per workgroup (1..4); grid = persistent workgroups
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid)
 {
     switch ((a.p.K + 15) / 16) {
@@ -510,6 +608,10 @@ static int blocks_per_cu()
 {
     int nb = 0;
     const size_t lds = fast_lds_bytes<NWK, 1, NC>();
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)recurrence_fast_kernel<NWK, 1, NC, false, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return 0;
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
         &nb, recurrence_fast_kernel<NWK, 1, NC, false, false>, WAVE * NWK, lds);
     return e == hipSuccess ? nb : 0;
@@ -519,12 +621,16 @@ static int blocks_per_cu()
 // workgroup, from the runtime's occupancy calculator.
 int fast_kernel_blocks_per_cu(int K, int nc)
 {
+#define ALPA_BPC(NWK_)                                                                        \
+    (nc == 4 ? blocks_per_cu<NWK_, 4>() : nc == 3 ? blocks_per_cu<NWK_, 3>()                     \
+     : nc == 2 ? blocks_per_cu<NWK_, 2>() : blocks_per_cu<NWK_, 1>())
     switch ((K + 15) / 16) {
-    case 1: return nc == 2 ? blocks_per_cu<1, 2>() : blocks_per_cu<1, 1>();
-    case 2: return nc == 2 ? blocks_per_cu<2, 2>() : blocks_per_cu<2, 1>();
-    case 3: return nc == 2 ? blocks_per_cu<3, 2>() : blocks_per_cu<3, 1>();
-    default: return nc == 2 ? blocks_per_cu<4, 2>() : blocks_per_cu<4, 1>();
+    case 1: return ALPA_BPC(1);
+    case 2: return ALPA_BPC(2);
+    case 3: return ALPA_BPC(3);
+    default: return ALPA_BPC(4);
     }
+#undef ALPA_BPC
 }
 
 }  // namespace alpa
