@@ -48,9 +48,9 @@ struct alpa_dp {
     int n_cu = 0;
     bool fast_ok = false;
     int KP = 0;
-    int fast_grid_max[5] = {0, 0, 0, 0, 0}, generic_grid_max = 0;   // [nc] for nc = 1..4
+    int fast_grid_max[3] = {0, 0, 0}, generic_grid_max = 0;   // [nc] for nc = 1, 2
 
-    int32_t *d_table = nullptr, *d_sizes = nullptr, *d_recs = nullptr;
+    int32_t *d_table = nullptr, *d_sizes = nullptr, *d_recs = nullptr, *d_gmin = nullptr;
     PrepBuffers pb{};
     int32_t *d_distinct = nullptr;
     uint32_t *d_ncount = nullptr;   // [2]: distinct table values, distinct caller candidates
@@ -166,7 +166,7 @@ extern "C" void alpa_dp_destroy(alpa_dp_t *h)
     (void)hipStreamSynchronize(h->stream);
     free_candidate_arrays(h);
     free_sweep_arrays(h);
-    (void)hipFree(h->d_table); (void)hipFree(h->d_sizes); (void)hipFree(h->d_recs);
+    (void)hipFree(h->d_table); (void)hipFree(h->d_sizes); (void)hipFree(h->d_recs); (void)hipFree(h->d_gmin);
     (void)hipFree(h->pb.hist); (void)hipFree(h->d_ncount); (void)hipFree(h->d_state); (void)hipFree(h->d_scratch);
     (void)hipFree(h->d_Fall); (void)hipFree(h->d_tmpFS); (void)hipFree(h->d_plan_tmp); (void)hipFree(h->d_best_plan);
     for (auto &e : h->ev) if (e) (void)hipEventDestroy(e);
@@ -242,9 +242,10 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
     if (h->fast_ok) {
         h->KP = 16 * ((K + 15) / 16);
         HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
+        HIPCHK(hipMalloc(&h->d_gmin, fast_group_min_ints(K, S) * 4));
         HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
-        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
-        for (int nc = 1; nc <= 4; ++nc) {
+        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs, h->d_gmin));
+        for (int nc = 1; nc <= 2; ++nc) {
             int per_cu = fast_kernel_blocks_per_cu(K, nc);
             if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
             if (const char *e = getenv("ALPA_DP_WG_PER_CU")) {   // tuning aid
@@ -383,7 +384,7 @@ extern "C" int alpa_dp_restrict_equal_layers(alpa_dp_t *h)
     HIPCHK(launch_equal_layer_mask(h->stream, h->d_table, K, S));
     if (h->fast_ok) {
         HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
-        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs));
+        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs, h->d_gmin));
     }
     // the candidate list changes with the table; the running best belonged to the old one
     int rc = queue_table_candidates(h);
@@ -492,11 +493,11 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             // two candidates per workgroup share every scalar load; worth it once there are
             // enough candidates to fill the device twice over that way
             int nc = (bound >= 4 * h->fast_grid_max[2]) ? 2 : 1;
-            if (const char *e = getenv("ALPA_DP_NC")) nc = std::min(4, std::max(1, atoi(e)));   // tuning aid
+            if (const char *e = getenv("ALPA_DP_NC")) nc = atoi(e) == 2 ? 2 : 1;   // tuning aid
             const int grid = std::max(1, std::min((bound + nc - 1) / nc, h->fast_grid_max[nc]));
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
-                        /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr, nullptr};
+                        /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr, nullptr, h->d_gmin};
             HIPCHK(launch_recurrence_fast(st, fa, (flags & ALPA_DP_COUNT_WORK) ? FAST_MODE_COUNT
                                                                               : FAST_MODE_BATCH,
                                           nc, grid));
@@ -516,7 +517,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             const size_t slab = (size_t)(p.Smax + 1) * (size_t)(p.K + 2) * (p.D + 1);
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_sw_c, h->d_sw_n, h->d_sw_n + 1,
                         &h->d_state->wave_relax, nullptr, 0, 0, h->d_sw_FS,
-                        h->d_sw_FS + (n_B + 1), n_B, h->d_sw_Fall, h->d_sw_s};
+                        h->d_sw_FS + (n_B + 1), n_B, h->d_sw_Fall, h->d_sw_s, h->d_gmin};
             HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1, std::min(n_B, h->n_cu)));
             HIPCHK(launch_plan_walk_many(st, p, h->d_table, h->d_sizes, h->d_sw_state,
                                          h->d_sw_Fall, slab, h->d_sw_plans, n_B));
@@ -544,7 +545,8 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
         FastArgs fa{p, h->d_recs, h->d_sizes, &h->d_state->best_c,
                     &h->d_state->plan_n, &h->d_state->plan_ticket, &h->d_state->wave_relax,
-                    nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall, &h->d_state->best_s};
+                    nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall, &h->d_state->best_s,
+                    h->d_gmin};
         HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1, 1));
     } else {
         HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, &h->d_state->best_c,

@@ -136,8 +136,9 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
 hipError_t launch_equal_layer_mask(hipStream_t st, int32_t *table, int K, int S);
 
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
-                              int32_t *recs);
+                              int32_t *recs, int32_t *group_min);
 size_t fast_table_ints(int K, int S);    // size of the column-record array, padding included
+size_t fast_group_min_ints(int K, int S);   // size of the early-stop table
 
 hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int32_t *table,
                                      const int32_t *sizes, const int32_t *cand,
@@ -157,6 +158,7 @@ struct FastArgs {
     // stops at layer s_top_p[j], the winner's number of stages (device memory)
     int32_t *F_all;
     const int32_t *s_top_p;
+    const int32_t *group_min;   // early-stop table (launch_repack_fast)
 };
 enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);

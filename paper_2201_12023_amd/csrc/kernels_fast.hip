@@ -34,6 +34,7 @@ namespace alpa {
 typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-load path
 
 constexpr int HB_INTS = 10;
+constexpr int END_SHAPES = 12;         // shapes covered by the early-stop table (3 registers)
 
 __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int S, int KP,
                                    int32_t *__restrict__ recs)
@@ -62,6 +63,31 @@ __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int
         }
         rec[0] = mn;
         rec[1] = (mx < 0) ? DEV_INF : mx;
+    }
+}
+
+// Second pass of the repack.  For every (q, half-block, group j of 8 columns, s) the minimum of
+// t_intra over the half-block's first layers and all last layers >= 8j: a candidate below it
+// finds nothing in column 8j or any later one, so the column loops of that (s, q, half-block)
+// can stop there.  Layout g[q][hb][j][s - 1] with the s axis padded to 64: the kernel reads it
+// with lane = s - 1.
+constexpr int END_GROUPS = 8;                          // groups of 8 columns (K <= 64)
+__global__ void repack_group_min_kernel(int K, int S, int KP, const int32_t *__restrict__ recs,
+                                        int32_t *__restrict__ g)
+{
+    const int NHB = KP / 8;
+    const int total = S * NHB * WAVE;                  // one thread per (q, hb, s - 1)
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
+        const int s1 = e % WAVE;
+        const int hb = (e / WAVE) % NHB;
+        const int q = e / (WAVE * NHB);
+        int32_t run = 0x3f3f3f3f;                      // above DEV_INF: never alive
+        for (int j = END_GROUPS - 1; j >= 0; --j) {
+            if (s1 < K)
+                for (int i = min(K, 8 * j + 8) - 1; i >= 8 * j; --i)
+                    run = min(run, recs[((((long long)s1 * S + q) * K + i) * NHB + hb) * HB_INTS]);
+            g[((q * NHB + hb) * END_GROUPS + j) * WAVE + s1] = run;
+        }
     }
 }
 
@@ -185,12 +211,14 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // DUMP = also store every layer to F_all (plan recovery, NC = 1); COUNT = tally executed
 // half-blocks.  Fmin / Sbest have a spare slot at index dummy_idx for results nobody owns.
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
-__global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
+__global__ __launch_bounds__(WAVE * NWK * WI) __attribute__((amdgpu_waves_per_eu(4)))
+void recurrence_fast_kernel(
     Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
     unsigned long long *wave_relax, int64_t *chunk_min, int prune, int descending,
     int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest, int dummy_idx,
-    int32_t *__restrict__ F_all, const int32_t *__restrict__ s_top_p)
+    int32_t *__restrict__ F_all, const int32_t *__restrict__ s_top_p,
+    const int32_t *__restrict__ group_min)
 {
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     constexpr int NT = WAVE * NWK * WI;
@@ -199,6 +227,7 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
     extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
     __shared__ int32_t sh_tk[NT];
     __shared__ int32_t sh_skip[NWK * WI];
+    __shared__ int32_t sh_ends[NWK * WI * (END_SHAPES / 4) * WAVE];   // early-stop table
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -269,6 +298,34 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
             for (int x = tid; x < total; x += NT) F_out[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
             __syncthreads();
         }
+        // Where the column loops may stop: lane s - 1 gets, for every shape q and the wave's two
+        // half-blocks, the number of leading 8-column groups in which the largest candidate
+        // still finds an entry (4 bits each, shape q at bits 8 (q % 4) of word q / 4 of the
+        // wave's rows in sh_ends; only the wave itself reads them, so no barrier is needed).
+        // Shapes beyond END_SHAPES are not covered (their loops run to the end).
+        {
+            const int32_t cmax = c[NC - 1];
+            constexpr int NHB = KP / 8;
+            int32_t word = 0;
+#pragma nounroll
+            for (int q = 0; q < END_SHAPES; ++q) {     // rows of shapes >= S are never read
+                if (q < S) {
+                    const int32_t *gA = group_min + ((q * NHB + hbA) * END_GROUPS) * WAVE + lane;
+                    const int32_t *gB = group_min + ((q * NHB + hbB) * END_GROUPS) * WAVE + lane;
+                    int nA = 0, nB = 0;
+#pragma unroll
+                    for (int j = 0; j < END_GROUPS; ++j) {
+                        nA += gA[j * WAVE] <= cmax ? 1 : 0;
+                        nB += gB[j * WAVE] <= cmax ? 1 : 0;
+                    }
+                    word |= (nA | (nB << 4)) << (8 * (q & 3));
+                }
+                if ((q & 3) == 3) {                    // four shapes per word
+                    sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + lane] = word;
+                    word = 0;
+                }
+            }
+        }
         int32_t best[NC], sbest[NC];
 #pragma unroll
         for (int e = 0; e < NC; ++e) { best[e] = DEV_INF; sbest[e] = 0; }
@@ -293,10 +350,17 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
             if (WI > 1) {
                 for (int x = tid; x < NC * ROWS * WAVE; x += NT) Fnext[x] = DEV_INF;
             }
+            // Two passes over the shapes: first those whose updates go candidate by candidate,
+            // then those served by the packed form (one pass at a time keeps each loop's set
+            // of live accumulators, and with it the register traffic between them, small).
+            auto shapes_pass = [&](auto PASS_PACKED) {
+            constexpr bool PASS_P = decltype(PASS_PACKED)::value;
             for (int q = wi; q < S; q += WI) {          // wave group wi takes every WI-th shape
                 const int a = sizes[q];
                 if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
                 if (i0 > i_hi) continue;
+                // packed when every device count the shape can still serve is in the window
+                if ((PACK && s > 1 && a + s - 2 >= pk_base) != PASS_P) continue;
                 constexpr int STEP = REC;
                 const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
                 cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
@@ -316,27 +380,34 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                     }
                     continue;
                 }
+                // first column group without anything for the largest candidate, per half-block
+                int endA = K, endB = K;
+                if (q < END_SHAPES) {
+                    const int bits = __builtin_amdgcn_readfirstlane(
+                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + s - 1]) >> (8 * (q & 3));
+                    endA = needA ? 8 * (bits & 15) : 0;
+                    endB = needB ? 8 * ((bits >> 4) & 15) : 0;
+                }
                 auto columns = [&](auto PK) {
                     // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
                     // their LDS rows; while one batch is computed the loads of the next are in
-                    // flight, so every wait is covered by a whole batch of updates.  Where only
-                    // half-block A is reached (last layer < rowB) a batch is the A halves of two
-                    // columns, afterwards it is the A and B halves of one column.  Loads past
-                    // the last column land in the padding and are dropped.
+                    // flight, so every wait is covered by a whole batch of updates.  Three
+                    // phases: columns that reach only half-block A (a batch = the A halves of two
+                    // columns), columns in which both half-blocks still have entries for the
+                    // largest candidate (a batch = the A and B halves of one column), and the
+                    // columns in which only half-block B has (a batch = the B halves of two
+                    // columns).  Loads past the last column land in the padding and are dropped.
                     // P: the two candidates share each pass (see relax8p); one LDS row per column
                     constexpr bool P = decltype(PK)::value;
                     constexpr int NF = P ? 1 : NC;
                     const int dl = P ? pk_dl : lane;       // d - 1 served by this lane
                     const bool live = dl >= a;             // d - a_q >= 1
-                    const int32_t *frow = Fprev + (P ? pk_cand_off : 0) + (live ? dl - a : 0) +
-                                          (i0 + 1) * WAVE;                         // row i+1
-                    struct Batch { HalfColumn X, Y; int32_t fX[NF], fY[NF]; } b0, b1;
-                    auto rows = [&](int32_t (&dst)[NF], int col) {     // col: columns ahead of frow
-    #pragma unroll
-                        for (int e = 0; e < NF; ++e) dst[e] = frow[(e * ROWS + col) * WAVE];
+                    auto row_ptr = [&](int i) {            // operand row of column i: row i + 1
+                        return Fprev + (P ? pk_cand_off : 0) + (live ? dl - a : 0) + (i + 1) * WAVE;
                     };
+                    struct Batch { HalfColumn X, Y; int32_t fX[NF], fY[NF]; } b0, b1;
                     auto operands = [&](const int32_t (&src)[NF]) {
-    #pragma unroll
+#pragma unroll
                         for (int e = 0; e < NF; ++e) G[e] = live ? src[e] : DEV_INF;
                     };
                     auto relax = [&](int off, HalfColumn &h, int32_t mn) {
@@ -345,105 +416,113 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
                         else
                             relax8<NC, COUNT>(acc, off, h.t, mn, h.mx, G, c, n_blocks);
                     };
-                    auto settle_batch = [&](const Batch &b) {
-                        settle(b.X, b.fX[0]);
-                        settle(b.Y, b.fY[0]);
-                    };
-                    // --- columns that only reach half-block A: slots = columns i and i + 1
-                    auto load_AA = [&](Batch &b, int col) {
-                        rows(b.fX, col);
-                        rows(b.fY, col + 1);
-                        load_half(b.X, pA + (size_t)col * STEP);
-                        load_half(b.Y, pA + (size_t)(col + 1) * STEP);
-                        fence_loads();
-                    };
-                    auto compute_AA = [&](Batch &b) {
-                        operands(b.fX);
-                        relax(0, b.X, mnA(b.X));
-                        operands(b.fY);
-                        relax(0, b.Y, mnA(b.Y));
-                    };
-                    const int n1 = max(0, min(rowB - i0, ncol));
-                    int left = n1;
-                    if (DUMP && !needA) {                  // nothing to do in this phase
-                        left = 0;
-                        pA += (size_t)n1 * STEP;
-                        frow += n1 * WAVE;
-                    }
-                    if (left >= 2) {
-                        load_AA(b0, 0);
-                        for (; left >= 4; left -= 4) {
-                            settle_batch(b0);
-                            load_AA(b1, 2);
-                            compute_AA(b0);
-                            settle_batch(b1);
-                            load_AA(b0, 4);
-                            compute_AA(b1);
-                            pA += 4 * STEP;
-                            frow += 4 * WAVE;
-                        }
+                    // `count` columns from the one p / frow point at, one half-block (acc rows
+                    // off..off+7) only
+                    auto single = [&](int off, cptr_t p, const int32_t *frow, int count, auto mnf) {
+                        auto rows = [&](int32_t (&dst)[NF], int col) {
+#pragma unroll
+                            for (int e = 0; e < NF; ++e) dst[e] = frow[(e * ROWS + col) * WAVE];
+                        };
+                        auto load2 = [&](Batch &b, int col) {
+                            rows(b.fX, col);
+                            rows(b.fY, col + 1);
+                            load_half(b.X, p + (size_t)col * STEP);
+                            load_half(b.Y, p + (size_t)(col + 1) * STEP);
+                            fence_loads();
+                        };
+                        auto compute2 = [&](Batch &b) {
+                            operands(b.fX);
+                            relax(off, b.X, mnf(b.X));
+                            operands(b.fY);
+                            relax(off, b.Y, mnf(b.Y));
+                        };
+                        auto settle2 = [&](const Batch &b) {
+                            settle(b.X, b.fX[0]);
+                            settle(b.Y, b.fY[0]);
+                        };
+                        int left = count;
                         if (left >= 2) {
-                            settle_batch(b0);
-                            compute_AA(b0);
-                            pA += 2 * STEP;
-                            frow += 2 * WAVE;
-                            left -= 2;
-                        }
-                    }
-                    if (left == 1) {
-                        rows(b0.fX, 0);
-                        load_half(b0.X, pA);
-                        operands(b0.fX);
-                        relax(0, b0.X, mnA(b0.X));
-                        pA += STEP;
-                        frow += WAVE;
-                    }
-                    // --- columns that reach both half-blocks: slots = halves A and B of a column
-                    pB += (size_t)n1 * STEP;
-                    auto load_AB = [&](Batch &b, int col) {
-                        rows(b.fX, col);
-                        load_half(b.X, pA + (size_t)col * STEP);
-                        load_half(b.Y, pB + (size_t)col * STEP);
-                        fence_loads();
-                    };
-                    auto compute_AB = [&](Batch &b) {
-                        operands(b.fX);
-                        relax(0, b.X, mnA(b.X));
-                        relax(8, b.Y, mnB(b.Y));
-                    };
-                    auto settle_AB = [&](const Batch &b) {
-                        settle(b.X, b.fX[0]);
-                        settle(b.Y);
-                    };
-                    left = ncol - n1;
-                    if (left >= 1) {
-                        load_AB(b0, 0);
-                        for (; left >= 2; left -= 2) {
-                            settle_AB(b0);
-                            load_AB(b1, 1);
-                            compute_AB(b0);
-                            settle_AB(b1);
-                            load_AB(b0, 2);
-                            compute_AB(b1);
-                            pA += 2 * STEP;
-                            pB += 2 * STEP;
-                            frow += 2 * WAVE;
+                            load2(b0, 0);
+                            for (; left >= 4; left -= 4) {
+                                settle2(b0);
+                                load2(b1, 2);
+                                compute2(b0);
+                                settle2(b1);
+                                load2(b0, 4);
+                                compute2(b1);
+                                p += 4 * STEP;
+                                frow += 4 * WAVE;
+                            }
+                            if (left >= 2) {
+                                settle2(b0);
+                                compute2(b0);
+                                p += 2 * STEP;
+                                frow += 2 * WAVE;
+                                left -= 2;
+                            }
                         }
                         if (left == 1) {
-                            settle_AB(b0);
-                            compute_AB(b0);
+                            rows(b0.fX, 0);
+                            load_half(b0.X, p);
+                            operands(b0.fX);
+                            relax(off, b0.X, mnf(b0.X));
+                        }
+                    };
+                    // columns of each phase; endA / endB bound where the half-blocks still
+                    // have something for the largest candidate
+                    const int n1 = max(0, min(rowB - i0, ncol));       // reach half-block A only
+                    const int cAB = i0 + n1;                           // first column reaching B
+                    const int stopAB = endA > endB ? endA : min(endA, endB);
+                    const int nAB = max(0, min(ncol - n1, stopAB - cAB));
+                    const int cB = cAB + nAB;                          // B alone from here
+                    const int nB = max(0, min(i_hi + 1, endB) - cB);
+                    single(0, pA, row_ptr(i0), max(0, min(n1, endA - i0)), mnA);
+                    {
+                        cptr_t p1 = pA + (size_t)n1 * STEP, p2 = pB + (size_t)n1 * STEP;
+                        const int32_t *frow = row_ptr(cAB);
+                        auto load_AB = [&](Batch &b, int col) {
+#pragma unroll
+                            for (int e = 0; e < NF; ++e) b.fX[e] = frow[(e * ROWS + col) * WAVE];
+                            load_half(b.X, p1 + (size_t)col * STEP);
+                            load_half(b.Y, p2 + (size_t)col * STEP);
+                            fence_loads();
+                        };
+                        auto compute_AB = [&](Batch &b) {
+                            operands(b.fX);
+                            relax(0, b.X, mnA(b.X));
+                            relax(8, b.Y, mnB(b.Y));
+                        };
+                        auto settle_AB = [&](const Batch &b) {
+                            settle(b.X, b.fX[0]);
+                            settle(b.Y);
+                        };
+                        int left = nAB;
+                        if (left >= 1) {
+                            load_AB(b0, 0);
+                            for (; left >= 2; left -= 2) {
+                                settle_AB(b0);
+                                load_AB(b1, 1);
+                                compute_AB(b0);
+                                settle_AB(b1);
+                                load_AB(b0, 2);
+                                compute_AB(b1);
+                                p1 += 2 * STEP;
+                                p2 += 2 * STEP;
+                                frow += 2 * WAVE;
+                            }
+                            if (left == 1) {
+                                settle_AB(b0);
+                                compute_AB(b0);
+                            }
                         }
                     }
-            
+                    single(8, pB + (size_t)(cB - i0) * STEP, row_ptr(cB), nB, mnB);
                 };
-                if constexpr (PACK) {
-                    // packed when every device count the shape can still serve is in the window
-                    if (a + s - 2 >= pk_base) columns(std::true_type{});
-                    else columns(std::false_type{});
-                } else {
-                    columns(std::false_type{});
-                }
+                columns(PASS_PACKED);
             }
+            };
+            shapes_pass(std::false_type{});
+            if constexpr (PACK) shapes_pass(std::true_type{});
             if (PACK) {
                 // lane l (d - 1 = l) takes candidate e's packed result from lane 32 e + l - pk_base
                 const int rel = lane - pk_base;
@@ -529,13 +608,21 @@ __global__ __launch_bounds__(WAVE * NWK * WI) void recurrence_fast_kernel(
 }
 
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
-                              int32_t *recs)
+                              int32_t *recs, int32_t *group_min)
 {
     long long total = (long long)K * K * S * (KP / 8);
     int grid = (int)((total + 255) / 256);
     if (grid > 8192) grid = 8192;
     hipLaunchKernelGGL(repack_fast_kernel, dim3(grid), dim3(256), 0, st, table, K, S, KP, recs);
+    const int n_chains = S * (KP / 8) * WAVE;
+    hipLaunchKernelGGL(repack_group_min_kernel, dim3((n_chains + 63) / 64), dim3(64), 0, st, K, S,
+                       KP, recs, group_min);
     return hipGetLastError();
+}
+
+size_t fast_group_min_ints(int K, int S)
+{
+    return (size_t)S * ((K + 15) / 16 * 2) * END_GROUPS * WAVE;
 }
 
 size_t fast_table_ints(int K, int S)
@@ -565,7 +652,7 @@ static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
     hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>), dim3(grid),
                        dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
                        a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
-                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p);
+                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p, a.group_min);
     return hipGetLastError();
 }
 
@@ -575,23 +662,15 @@ static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc
     switch (mode) {
     case FAST_MODE_PLAN: return launch_one<NWK, PLAN_WI, 1, true, false>(st, a, grid);
     case FAST_MODE_COUNT:
-        switch (nc) {
-        case 4: return launch_one<NWK, 1, 4, false, true>(st, a, grid);
-        case 3: return launch_one<NWK, 1, 3, false, true>(st, a, grid);
-        case 2: return launch_one<NWK, 1, 2, false, true>(st, a, grid);
-        default: return launch_one<NWK, 1, 1, false, true>(st, a, grid);
-        }
+        return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
+                       : launch_one<NWK, 1, 1, false, true>(st, a, grid);
     default:
-        switch (nc) {
-        case 4: return launch_one<NWK, 1, 4, false, false>(st, a, grid);
-        case 3: return launch_one<NWK, 1, 3, false, false>(st, a, grid);
-        case 2: return launch_one<NWK, 1, 2, false, false>(st, a, grid);
-        default: return launch_one<NWK, 1, 1, false, false>(st, a, grid);
-        }
+        return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
+                       : launch_one<NWK, 1, 1, false, false>(st, a, grid);
     }
 }
 
-// nc = candidates per workgroup (1..4); grid = persistent workgroups
+// nc = candidates per workgroup (1 or 2); grid = persistent workgroups
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid)
 {
     switch ((a.p.K + 15) / 16) {
@@ -621,9 +700,7 @@ static int blocks_per_cu()
 // workgroup, from the runtime's occupancy calculator.
 int fast_kernel_blocks_per_cu(int K, int nc)
 {
-#define ALPA_BPC(NWK_)                                                                        \
-    (nc == 4 ? blocks_per_cu<NWK_, 4>() : nc == 3 ? blocks_per_cu<NWK_, 3>()                     \
-     : nc == 2 ? blocks_per_cu<NWK_, 2>() : blocks_per_cu<NWK_, 1>())
+#define ALPA_BPC(NWK_) (nc == 2 ? blocks_per_cu<NWK_, 2>() : blocks_per_cu<NWK_, 1>())
     switch ((K + 15) / 16) {
     case 1: return ALPA_BPC(1);
     case 2: return ALPA_BPC(2);
