@@ -56,6 +56,8 @@ RANDOM_CASES = [
     (0, 1, 1, 1), (1, 2, 1, 2), (2, 3, 2, 2), (3, 5, 1, 4), (4, 6, 2, 4), (5, 7, 3, 2),
     (6, 9, 3, 4), (7, 12, 2, 8), (8, 17, 4, 4), (9, 16, 1, 8), (10, 33, 2, 2), (11, 20, 5, 4),
     (12, 10, 8, 8), (13, 40, 3, 8), (14, 64, 1, 2), (15, 13, 7, 8),
+    # more shapes than the register/LDS kernel's early-stop table covers (18, then the maximum 64)
+    (16, 30, 16, 4), (17, 20, 64, 1), (18, 64, 5, 8), (19, 57, 8, 8),
 ]
 
 
