@@ -222,7 +222,7 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
     HIPCHK(hipMemcpyAsync(h->d_sizes, sizes.data(), (size_t)S * 4, hipMemcpyHostToDevice,
                           h->stream));
     HIPCHK(hipStreamSynchronize(h->stream));      // `sizes` may go away after the return
-    HIPCHK(hipMalloc(&h->pb.hist, (256 * 256 + 256) * 4));   // counts + digit totals
+    HIPCHK(hipMalloc(&h->pb.hist, (SORT_RADIX * SORT_SLICES + SORT_RADIX) * 4));   // counts + totals
     HIPCHK(hipMalloc(&h->d_ncount, 2 * 4));
     HIPCHK(hipMalloc(&h->d_state, sizeof(SolveState)));
     HIPCHK(hipMemsetAsync(h->d_state, 0, sizeof(SolveState), h->stream));

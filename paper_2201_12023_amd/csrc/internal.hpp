@@ -109,9 +109,12 @@ __device__ __forceinline__ int64_t wave_prefix_min_i64(int64_t v, int lane)
 
 // ---- host-side launchers (callers validate sizes first; none of these synchronises)
 
+constexpr int SORT_SLICES = 1024;        // one-wave slices of the radix sort
+constexpr int SORT_RADIX = 256;          // 8-bit digits
+
 struct PrepBuffers {
     int32_t *keys[2];        // [cap] each
-    uint32_t *hist;          // [256 * 256] slice counts + [256] digit totals
+    uint32_t *hist;          // [SORT_RADIX * SORT_SLICES] slice counts + [SORT_RADIX] digit totals
     uint32_t *block_cnt;     // [cap / 4096 + 2]
     int cap;
 };

@@ -120,23 +120,36 @@ __global__ __launch_bounds__(256) void recurrence_generic_kernel(
 
 // ---------------------------------------------------------------- Eq. 4 + best selection
 
-// One wave.  T(c_j) = Fmin_j + (B - 1) * c_j (Eq. 4); with pruning on, the processed set
+// One block.  T(c_j) = Fmin_j + (B - 1) * c_j (Eq. 4); with pruning on, the processed set
 // is the prefix [0, p) where p is the first index with B * c_p >= min_{j < p} T(c_j), as
 // in the sequential loop of Alg. 1; the winner is the lowest T, lowest index on ties
 // (strict "<" of Alg. 1 while ascending).
-// `T` may be null (no per-candidate output).
+// `T` may be null (no per-candidate output).  One block of SEL_THREADS threads, tiles of
+// SEL_THREADS candidates: prefix minimum inside each wave, the waves' totals through LDS, the
+// first index that fires and the arg-min through LDS atomics.
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / WAVE;
+
 __device__ __forceinline__ void eq4_select(int B, int n, const int32_t *__restrict__ cand,
                                            const int32_t *__restrict__ Fmin,
                                            const int32_t *__restrict__ Sbest, SolveState *state,
                                            int prune, int64_t *__restrict__ T)
 {
-    const int lane = threadIdx.x;
-    int64_t carry = INF_I64;          // min of T over all earlier chunks
+    __shared__ int64_t sh_wave_min[SEL_WAVES];
+    __shared__ int sh_first_fire;
+    __shared__ unsigned long long sh_best;             // lowest processed T of the tile
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid >> 6;
+    int64_t carry = INF_I64;          // min of T over all earlier tiles
     int n_proc = n;
     int64_t bestT = INF_I64;
     int bestj = -1;
-    for (int j0 = 0; j0 < n; j0 += WAVE) {
-        const int j = j0 + lane;
+    bool stopped = false;             // block-uniform
+    for (int j0 = 0; j0 < n; j0 += SEL_THREADS) {
+        const int j = j0 + tid;
+        if (stopped) {                // everything after the break is not evaluated
+            if (T && j < n) T[j] = INF_I64;
+            continue;
+        }
         int64_t t = INF_I64, bc = 0;
         if (j < n) {
             const int32_t f = Fmin[j], c = cand[j];
@@ -144,34 +157,50 @@ __device__ __forceinline__ void eq4_select(int B, int n, const int32_t *__restri
             bc = (int64_t)B * (int64_t)c;
         }
         const int64_t incl = wave_prefix_min_i64(t, lane);
-        // exclusive prefix minimum, including earlier chunks
-        int lo = __shfl_up((int)(uint32_t)(uint64_t)incl, 1, 64);
-        int hi = __shfl_up((int)((uint64_t)incl >> 32), 1, 64);
+        if (tid == 0) { sh_first_fire = INT32_MAX; sh_best = ~0ull; }
+        if (lane == WAVE - 1) sh_wave_min[w] = incl;
+        __syncthreads();
+        // exclusive prefix minimum: earlier tiles, earlier waves of this tile, earlier lanes
+        int lo = __shfl_up(lo32(incl), 1, 64);
+        int hi = __shfl_up(hi32(incl), 1, 64);
         int64_t excl = (lane == 0) ? INF_I64 : i64_from(lo, hi);
         excl = min64(excl, carry);
+        int64_t tile_min = INF_I64;
+        for (int x = 0; x < SEL_WAVES; ++x) {
+            const int64_t m = sh_wave_min[x];
+            if (x < w) excl = min64(excl, m);
+            tile_min = min64(tile_min, m);
+        }
         const bool fire = prune && j < n && excl != INF_I64 && bc >= excl;
-        const uint64_t fm = __ballot(fire);
-        int limit = WAVE;                               // lanes below `limit` are processed
-        if (fm) limit = __ffsll((unsigned long long)fm) - 1;
-        if (T && j < n) T[j] = (lane < limit) ? t : INF_I64;
-        // best among processed lanes of this chunk
-        int64_t tt = (lane < limit && j < n) ? t : INF_I64;
-        const int64_t m = wave_min_i64(tt);
-        if (m < bestT) {
-            const uint64_t eq = __ballot(tt == m);
+        if (fire) atomicMin(&sh_first_fire, j);
+        __syncthreads();
+        const int first = sh_first_fire;               // INT32_MAX if nobody fired
+        const bool processed = j < n && j < first;
+        if (T && j < n) T[j] = processed ? t : INF_I64;
+        // arg-min of the processed part of the tile in two steps: the lowest value (T >= 0, so
+        // it orders as unsigned), then the lowest index that has it
+        const int64_t tt = processed ? t : INF_I64;
+        const int64_t wm = wave_min_i64(tt);
+        if (lane == 0 && wm != INF_I64) atomicMin(&sh_best, (unsigned long long)wm);
+        __syncthreads();
+        const int64_t m = (int64_t)sh_best;            // ~0ull (= -1) if nothing finite
+        __syncthreads();
+        if (sh_best != ~0ull && m < bestT) {           // block-uniform
+            if (tid == 0) sh_first_fire = INT32_MAX;   // reused: lowest index with T == m
+            __syncthreads();
+            if (tt == m) atomicMin(&sh_first_fire, j);
+            __syncthreads();
             bestT = m;
-            bestj = j0 + __ffsll((unsigned long long)eq) - 1;
+            bestj = sh_first_fire;
         }
-        if (fm) {
-            n_proc = j0 + limit;
-            // everything after the break is not evaluated
-            if (T)
-                for (int x = j0 + WAVE + lane; x < n; x += WAVE) T[x] = INF_I64;
-            break;
+        __syncthreads();
+        if (first != INT32_MAX) {
+            n_proc = first;
+            stopped = true;
         }
-        carry = min64(carry, wave_min_i64(t));
+        carry = min64(carry, tile_min);
     }
-    if (lane == 0) {
+    if (tid == 0) {
         state->n_processed = n_proc;
         state->best_idx = bestj;
         state->best_T = bestT;
@@ -182,7 +211,7 @@ __device__ __forceinline__ void eq4_select(int B, int n, const int32_t *__restri
     }
 }
 
-__global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t *__restrict__ cand,
+__global__ __launch_bounds__(SEL_THREADS) void epilogue_kernel(Problem p, const int32_t *__restrict__ cand,
                                                         const int32_t *__restrict__ Fmin,
                                                         const int32_t *__restrict__ Sbest,
                                                         SolveState *state, int prune,
@@ -194,7 +223,7 @@ __global__ __launch_bounds__(WAVE) void epilogue_kernel(Problem p, const int32_t
 // Sweep over the number of microbatches: F of Eq. 3 does not depend on B, so one wave per
 // B value applies Eq. 4 and the selection to the same Fmin / Sbest.  states[b] receives the
 // winner for B_vals[b]; win_c / win_s are the compact copies the plan-recovery run reads.
-__global__ __launch_bounds__(WAVE) void sweep_epilogue_kernel(
+__global__ __launch_bounds__(SEL_THREADS) void sweep_epilogue_kernel(
     const int32_t *__restrict__ B_vals, const int32_t *__restrict__ n_cand_p,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ Fmin,
     const int32_t *__restrict__ Sbest, SolveState *states, int prune, int32_t *__restrict__ win_c,
@@ -368,8 +397,8 @@ hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand
                            const int32_t *Fmin, const int32_t *Sbest, SolveState *state, int prune,
                            int64_t *T)
 {
-    hipLaunchKernelGGL(epilogue_kernel, dim3(1), dim3(WAVE), 0, st, p, cand, Fmin, Sbest, state,
-                       prune, T);
+    hipLaunchKernelGGL(epilogue_kernel, dim3(1), dim3(SEL_THREADS), 0, st, p, cand, Fmin, Sbest,
+                       state, prune, T);
     return hipGetLastError();
 }
 
@@ -404,8 +433,8 @@ hipError_t launch_sweep_epilogue(hipStream_t st, const int32_t *B_vals, int n_B,
                                  const int32_t *Fmin, const int32_t *Sbest, SolveState *states,
                                  int prune, int32_t *win_c, int32_t *win_s)
 {
-    hipLaunchKernelGGL(sweep_epilogue_kernel, dim3(n_B), dim3(WAVE), 0, st, B_vals, n_cand_p, cand,
-                       Fmin, Sbest, states, prune, win_c, win_s);
+    hipLaunchKernelGGL(sweep_epilogue_kernel, dim3(n_B), dim3(SEL_THREADS), 0, st, B_vals,
+                       n_cand_p, cand, Fmin, Sbest, states, prune, win_c, win_s);
     return hipGetLastError();
 }
 

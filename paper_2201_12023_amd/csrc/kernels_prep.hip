@@ -10,8 +10,8 @@
 
 namespace alpa {
 
-constexpr int SORT_BLOCKS = 256;      // one wave each, contiguous slice per wave
-constexpr int RADIX = 256;
+constexpr int SORT_BLOCKS = SORT_SLICES;   // one wave each, contiguous slice per wave
+constexpr int RADIX = SORT_RADIX;
 
 // ---------------------------------------------------------------- gather
 
