@@ -33,9 +33,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
-    ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="measured HBM bytes per launch of the recurrence kernel (from a "
-                         "rocprofv3 --pmc run, see profiles/), reported as roofline.traffic")
+    ap.add_argument("--traffic-bytes", type=float, default=51.2e6,
+                    help="measured HBM bytes per launch of the recurrence kernel, reported as "
+                         "roofline.traffic; the default is the stored measurement for workload 4 "
+                         "(two rocprofv3 --pmc runs, profiles/recurrence_fast_kernel_workload4_"
+                         "counters.md); 0 = report null")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over t_max candidates; "
@@ -150,7 +152,7 @@ def main():
                                f"prune {'on' if w.prune else 'off'}, seed {w.seed}"},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12,
                      "unit": "Tlane-op/s (int32)", "frac": achieved / INT32_VALU_PEAK,
-                     "traffic": args.traffic_bytes, "kernel": "recurrence_fast_kernel",
+                     "traffic": (args.traffic_bytes or None) if args.workload == 4 else None, "kernel": "recurrence_fast_kernel",
                      "kernel_ms_avg": rec_avg},
         "extra": {"candidates_per_s": C / (dt / args.steps),
                   "cell_updates_per_s_alg1_dense": wc["n_dense"] * C / (dt / args.steps),
