@@ -248,6 +248,7 @@ void recurrence_fast_kernel(
     const int pk_dl = pk_base + (lane & 31);
     const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
     const bool half1 = lane >= 32;
+    const int32_t size_of_lane = sizes[min(lane, S - 1)];   // lane q holds a_q (S <= 64)
     const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
     const int n_groups = (n + NC - 1) / NC;
     unsigned long long n_blocks_total = 0;
@@ -350,17 +351,28 @@ void recurrence_fast_kernel(
             if (WI > 1) {
                 for (int x = tid; x < NC * ROWS * WAVE; x += NT) Fnext[x] = DEV_INF;
             }
+            bool packed_any = false;                   // a packed pass touched accP
             // Two passes over the shapes: first those whose updates go candidate by candidate,
             // then those served by the packed form (one pass at a time keeps each loop's set
             // of live accumulators, and with it the register traffic between them, small).
             auto shapes_pass = [&](auto PASS_PACKED) {
             constexpr bool PASS_P = decltype(PASS_PACKED)::value;
             for (int q = wi; q < S; q += WI) {          // wave group wi takes every WI-th shape
-                const int a = sizes[q];
+                const int a = __builtin_amdgcn_readlane(size_of_lane, q);
                 if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
                 if (i0 > i_hi) continue;
                 // packed when every device count the shape can still serve is in the window
                 if ((PACK && s > 1 && a + s - 2 >= pk_base) != PASS_P) continue;
+                // first column group without anything for the largest candidate, per half-block
+                int endA = K, endB = K;
+                if (q < END_SHAPES) {
+                    const int bits = __builtin_amdgcn_readfirstlane(
+                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + s - 1]) >> (8 * (q & 3));
+                    endA = needA ? 8 * (bits & 15) : 0;
+                    endB = needB ? 8 * ((bits >> 4) & 15) : 0;
+                }
+                if (s > 1 && endA <= i0 && endB <= rowB) continue;   // nothing alive in reach
+                if (PASS_P) packed_any = true;
                 constexpr int STEP = REC;
                 const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
                 cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
@@ -379,14 +391,6 @@ void recurrence_fast_kernel(
                         if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, mnB(hB), hB.mx, G, c, n_blocks);
                     }
                     continue;
-                }
-                // first column group without anything for the largest candidate, per half-block
-                int endA = K, endB = K;
-                if (q < END_SHAPES) {
-                    const int bits = __builtin_amdgcn_readfirstlane(
-                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + s - 1]) >> (8 * (q & 3));
-                    endA = needA ? 8 * (bits & 15) : 0;
-                    endB = needB ? 8 * ((bits >> 4) & 15) : 0;
                 }
                 auto columns = [&](auto PK) {
                     // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
@@ -523,7 +527,7 @@ void recurrence_fast_kernel(
             };
             shapes_pass(std::false_type{});
             if constexpr (PACK) shapes_pass(std::true_type{});
-            if (PACK) {
+            if (PACK && packed_any) {
                 // lane l (d - 1 = l) takes candidate e's packed result from lane 32 e + l - pk_base
                 const int rel = lane - pk_base;
                 const bool in_window = rel >= 0 && rel < 32;
