@@ -126,6 +126,8 @@ def main():
     B.alpa_cluster_layers(og.flop, og.src, og.dst, og.nbytes, 64, 500000)
     cl = B.alpa_cluster_layers(og.flop, og.src, og.dst, og.nbytes, 64, 500000)
 
+    valu_measured = B.alpa_dp_measure_valu_peak()
+
     # check against the stored oracle results for this workload, if present
     verified = None
     gpath = os.path.join(ROOT, "tests", "golden", f"workload_{args.workload}.json")
@@ -152,6 +154,8 @@ def main():
                                f"prune {'on' if w.prune else 'off'}, seed {w.seed}"},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": INT32_VALU_PEAK / 1e12,
                      "unit": "Tlane-op/s (int32)", "frac": achieved / INT32_VALU_PEAK,
+                     "peak_measured": valu_measured / 1e12,
+                     "frac_of_measured": achieved / valu_measured,
                      "traffic": (args.traffic_bytes or None) if args.workload == 4 else None, "kernel": "recurrence_fast_kernel",
                      "kernel_ms_avg": rec_avg},
         "extra": {"candidates_per_s": C / (dt / args.steps),

@@ -283,6 +283,14 @@ int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
 int alpa_place_submeshes(int N, int M, const alpa_shape_t *stage_shapes, int num_stages,
                          int32_t *out_row, int32_t *out_col);
 
+/*
+ * Measurement aid: sustained rate of the recurrence's two vector instructions (int32 add with a
+ * scalar operand, signed min) from a register-only kernel at full occupancy on the current
+ * device, in lane-operations per second, to set beside the nominal peak (compute units x 64
+ * lanes x clock).  Blocking, about 50 ms.  Errors: EINVAL (null pointer), EHIP.
+ */
+int alpa_dp_measure_valu_peak(double *out_lane_ops_per_s);
+
 #ifdef __cplusplus
 }
 #endif

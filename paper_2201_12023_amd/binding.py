@@ -30,7 +30,7 @@ SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table"
            "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
            "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
-           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_place_submeshes"]
+           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_place_submeshes", "alpa_dp_measure_valu_peak"]
 
 
 class alpa_shape_t(ctypes.Structure):
@@ -97,6 +97,7 @@ def load():
                                       ctypes.POINTER(ctypes.c_float)]
     L.alpa_place_submeshes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(alpa_shape_t),
                                        ctypes.c_int, vp, vp]
+    L.alpa_dp_measure_valu_peak.argtypes = [ctypes.POINTER(ctypes.c_double)]
     L.alpa_dp_destroy.argtypes = [vp]
     L.alpa_dp_destroy.restype = None
     L.alpa_dp_last_error.restype = ctypes.c_char_p
@@ -283,3 +284,10 @@ def alpa_place_submeshes(N, M, stage_shapes):
     col = np.zeros(max(n, 1), np.int32)
     _check(load().alpa_place_submeshes(int(N), int(M), arr, n, row.ctypes.data, col.ctypes.data))
     return [(int(r), int(c)) for r, c in zip(row[:n], col[:n])]
+
+
+def alpa_dp_measure_valu_peak() -> float:
+    """Sustained int32 add + min rate of the current device, lane-operations per second."""
+    out = ctypes.c_double()
+    _check(load().alpa_dp_measure_valu_peak(ctypes.byref(out)))
+    return float(out.value)

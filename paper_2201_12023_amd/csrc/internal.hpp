@@ -136,6 +136,7 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
                               const int64_t *mem_act, int K, int S, int O, int64_t mem_device,
                               int32_t *table, int32_t *max_finite);
 
+hipError_t launch_valu_peak(hipStream_t st, int grid, int iters, int32_t *sink);
 hipError_t launch_equal_layer_mask(hipStream_t st, int32_t *table, int K, int S);
 
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,

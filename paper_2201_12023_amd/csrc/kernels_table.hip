@@ -118,3 +118,50 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
 }
 
 }  // namespace alpa
+
+// ---------------------------------------------------------------- VALU peak probe
+
+// Register-only add + min chains (the two vector instructions of one cell-update, the add with
+// a scalar operand as in the recurrence kernel) at full occupancy: what the int32 vector ALU
+// can sustain, to set beside the nominal 256 CU x 64 lanes x clock figure.
+namespace alpa {
+
+struct Scalars16 { int32_t v[16]; };
+
+__global__ __launch_bounds__(256) void valu_peak_kernel(int iters, Scalars16 sv,
+                                                        int32_t *__restrict__ sink)
+{
+    int32_t a[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) a[u] = DEV_INF - (int)threadIdx.x - u;
+    int32_t g = (int32_t)threadIdx.x;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 8; ++rep) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) a[u] = min(a[u], sv.v[u] + g);   // 16 distinct scalar operands
+            // "everything may have changed": no repetition is folded away or fused with the next
+            asm volatile("" : "+v"(g), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]),
+                              "+v"(a[5]), "+v"(a[6]), "+v"(a[7]), "+v"(a[8]), "+v"(a[9]),
+                              "+v"(a[10]), "+v"(a[11]), "+v"(a[12]), "+v"(a[13]), "+v"(a[14]),
+                              "+v"(a[15]));
+        }
+        g = a[it & 15] ^ g;                       // keeps the chain from being folded
+        asm volatile("" : "+v"(g));
+    }
+    int32_t r = g;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) r = min(r, a[u]);
+    if (r == 0x12345678) sink[0] = r;             // never true in practice; keeps the work alive
+}
+
+// 256 add/min instructions per iteration and thread are counted (the two chain-breaking ones not)
+hipError_t launch_valu_peak(hipStream_t st, int grid, int iters, int32_t *sink)
+{
+    Scalars16 sv;
+    for (int u = 0; u < 16; ++u) sv.v[u] = 3 + 2 * u;
+    hipLaunchKernelGGL(valu_peak_kernel, dim3(grid), dim3(256), 0, st, iters, sv, sink);
+    return hipGetLastError();
+}
+
+}  // namespace alpa
