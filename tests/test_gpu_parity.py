@@ -280,3 +280,21 @@ def test_general_kernel_on_a_mesh_larger_than_64_devices():
         _same_plan(plan, p_ref)
     finally:
         B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("case", [(91, 256, 1, 2), (92, 5, 32, 32), (93, 40, 16, 16)],
+                         ids=["K256-1x2", "K5-32x32", "K40-16x16"])
+def test_general_kernel_at_the_size_limits(case):
+    """The largest K (256), the largest mesh (1024 devices, 37 shapes) and one in between."""
+    seed, K, N, M = case
+    w = W.random_problem(seed, K, N, M, inf_frac=0.2, value_hi=3000)
+    cand = oracle.quantiles(oracle.all_candidates(w.table, w.shapes), 6)
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand, prune, 6)
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            T, plan = B.alpa_dp_solve(h, cand, flags=B.ALPA_DP_PRUNE if prune else 0)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
