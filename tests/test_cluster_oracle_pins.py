@@ -98,3 +98,13 @@ def test_invariants(seed):
     src2 = np.append(g.src, g.src[0]).astype(np.int32); dst2 = np.append(g.dst, g.dst[0]).astype(np.int32)
     nb2 = np.append(g.nbytes, g.nbytes[0] // 2); nb2[0] -= nb2[-1]
     assert oracle.cluster(g.flop, src2, dst2, nb2, L, delta) == (G, V, first)
+
+
+def test_full_ties_go_to_the_earliest_cut():
+    """Four unit-FLOP operators, edges 0->1 (5), 1->2 (7), 2->3 (5), 0->3 (100), two layers.
+    Cut before op 1: layer 2 receives 0->1 and 0->3 = 105, FLOP 1|3, squares 10.
+    Cut before op 2: receives 1->2 and 0->3 = 107.
+    Cut before op 3: receives 2->3 and 0->3 = 105, FLOP 3|1, squares 10.
+    The first and the third tie in both components; the recurrence keeps the lowest i."""
+    G, V, first = oracle.cluster([1, 1, 1, 1], [0, 1, 2, 0], [1, 2, 3, 3], [5, 7, 5, 100], 2, 1000000)
+    assert (G, V, first) == (105, 10, [0, 1, 4])
