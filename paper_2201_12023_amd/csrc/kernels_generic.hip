@@ -30,8 +30,12 @@ __device__ void fill_layers(const Problem &p, const int32_t *__restrict__ table,
         for (int x = tid; x < LS; x += nt) {
             const int k = x / (D + 1), d = x - k * (D + 1);
             int32_t v = DEV_INF;
-            if (k >= 1 && k <= K && d >= 1) {
-                for (int i = k; i <= K; ++i) {
+            // s stages need s layers and s devices: cells with k > K - s + 1 or d < s stay
+            // infinite, and an operand F(s-1, i+1, .) can only be finite for K - i >= s - 1
+            // (for s = 1 only the "past the end" row i + 1 = K + 1 is)
+            if (k >= 1 && k <= K - s + 1 && d >= s) {
+                const int i_first = (s == 1) ? K : k, i_last = K - s + 1;
+                for (int i = i_first; i <= i_last; ++i) {
                     const int32_t *tp = tab_s + ((size_t)(k - 1) * K + (i - 1)) * S;
                     const int32_t *prow = prev + (i + 1) * (D + 1);
                     for (int q = 0; q < S; ++q) {
@@ -73,13 +77,14 @@ __device__ bool can_skip(const int64_t *chunk_min, int j, int32_t c, int B)
     return m != INF_I64 && (int64_t)B * (int64_t)c >= m;
 }
 
-__global__ __launch_bounds__(256) void recurrence_generic_kernel(
+constexpr int GENERIC_MAX_THREADS = 1024;
+__global__ __launch_bounds__(GENERIC_MAX_THREADS) void recurrence_generic_kernel(
     Problem p, const int32_t *__restrict__ table, const int32_t *__restrict__ sizes,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
     int64_t *chunk_min, int prune, int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest,
     int32_t *scratch, int n_layers)
 {
-    __shared__ int32_t sh_tk[256];
+    __shared__ int32_t sh_tk[GENERIC_MAX_THREADS];
     __shared__ int sh_skip[WAVE];
     const int LS = (p.K + 2) * (p.D + 1);
     int32_t *slot = scratch + (size_t)blockIdx.x * n_layers * LS;
@@ -388,7 +393,9 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
                                      int n_layers, int grid)
 {
-    hipLaunchKernelGGL(recurrence_generic_kernel, dim3(grid), dim3(256), 0, st, p, table, sizes,
+    // a lone workgroup (the plan-recovery run of one candidate) gets the widest block
+    const int threads = grid == 1 ? GENERIC_MAX_THREADS : 256;
+    hipLaunchKernelGGL(recurrence_generic_kernel, dim3(grid), dim3(threads), 0, st, p, table, sizes,
                        cand, n_cand_p, ticket, chunk_min, prune, Fmin, Sbest, scratch, n_layers);
     return hipGetLastError();
 }
