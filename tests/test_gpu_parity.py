@@ -298,3 +298,21 @@ def test_general_kernel_at_the_size_limits(case):
             _same_plan(plan, p_ref)
         finally:
             B.alpa_dp_destroy(h)
+
+
+def test_valu_peak_probe_and_readme_example():
+    rate = B.alpa_dp_measure_valu_peak()
+    assert 1e13 < rate < 1e14                      # tens of T lane-ops/s on any gfx950 part
+    assert B.load().alpa_dp_measure_valu_peak(None) == -1
+    # the usage example of the README: solve, then place the chosen submeshes
+    w = W.make_workload(2)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        T, plan = B.alpa_dp_solve(h, None, 0, B.ALPA_DP_PRUNE)
+        shapes = [tuple(int(x) for x in w.shapes[q]) for q in plan["shape_idx"]]
+        where = B.alpa_place_submeshes(w.N, w.M, shapes)
+        from oracle import placement
+        assert where == placement.place(w.N, w.M, shapes)
+        assert sum(n * m for n, m in shapes) == w.N * w.M
+    finally:
+        B.alpa_dp_destroy(h)
