@@ -316,3 +316,29 @@ def test_valu_peak_probe_and_readme_example():
         assert sum(n * m for n, m in shapes) == w.N * w.M
     finally:
         B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("case", [c for c in RANDOM_CASES if c[1] <= 64 and c[2] * c[3] <= 64],
+                         ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_random_tables_two_candidates_per_workgroup(case, monkeypatch):
+    """The register/LDS kernel takes two candidates per workgroup (and packs them into one
+    pass where it can) only for long candidate lists; the tuning variable forces that form
+    here, on unstructured tables where most half-blocks need the entry-wise filter, odd
+    candidate counts included."""
+    monkeypatch.setenv("ALPA_DP_NC", "2")
+    seed, K, N, M = case
+    w = W.random_problem(500 + seed, K, N, M, inf_frac=0.25, value_hi=[6, 80, 7000][seed % 3])
+    cand_ref = oracle.all_candidates(w.table, w.shapes)
+    if len(cand_ref) > 301:
+        cand_ref = oracle.quantiles(cand_ref, 301)
+    if len(cand_ref) == 0:
+        pytest.skip("no finite entry")
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            T, plan = B.alpa_dp_solve(h, cand_ref, flags=B.ALPA_DP_PRUNE if prune else 0)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
