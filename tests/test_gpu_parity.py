@@ -342,3 +342,51 @@ def test_random_tables_two_candidates_per_workgroup(case, monkeypatch):
             _same_plan(plan, p_ref)
         finally:
             B.alpa_dp_destroy(h)
+
+
+def test_two_handles_on_two_streams_do_not_disturb_each_other():
+    import torch
+    wa, wb = W.make_workload(2), W.random_problem(41, 30, 4, 4, inf_frac=0.2, value_hi=300)
+    ca = oracle.quantiles(oracle.all_candidates(wa.table, wa.shapes), 700)
+    cb = oracle.quantiles(oracle.all_candidates(wb.table, wb.shapes), 500)
+    Ta, pa = oracle.solve_parallel(wa.table, wa.N, wa.M, wa.B, wa.shapes, ca, False, 8)
+    Tb, pb = oracle.solve_parallel(wb.table, wb.N, wb.M, wb.B, wb.shapes, cb, False, 8)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ha = B.alpa_dp_create(wa.table, wa.K, wa.N, wa.M, wa.B, wa.shapes)
+    hb = B.alpa_dp_create(wb.table, wb.K, wb.N, wb.M, wb.B, wb.shapes)
+    try:
+        B.alpa_dp_set_stream(ha, sa)
+        B.alpa_dp_set_stream(hb, sb)
+        da = torch.from_numpy(ca.copy()).cuda(); db = torch.from_numpy(cb.copy()).cuda()
+        oa = torch.empty(len(ca), dtype=torch.int64, device="cuda")
+        ob = torch.empty(len(cb), dtype=torch.int64, device="cuda")
+        qa = torch.zeros(B.PLAN_BYTES, dtype=torch.uint8, device="cuda")
+        qb = torch.zeros(B.PLAN_BYTES, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(5):                         # queued alternately, nothing waited for
+            B.alpa_dp_solve_dev(ha, da, len(ca), 0, oa, qa)
+            B.alpa_dp_solve_dev(hb, db, len(cb), 0, ob, qb)
+        sa.synchronize(); sb.synchronize()
+        assert (oa.cpu().numpy() == Ta).all() and (ob.cpu().numpy() == Tb).all()
+        _same_plan(B.plan_from_bytes(qa.cpu().numpy().tobytes()), pa)
+        _same_plan(B.plan_from_bytes(qb.cpu().numpy().tobytes()), pb)
+    finally:
+        B.alpa_dp_destroy(ha)
+        B.alpa_dp_destroy(hb)
+
+
+def test_create_and_destroy_give_the_memory_back():
+    import torch
+    w = W.make_workload(2)
+    def cycle(n):
+        for _ in range(n):
+            h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+            B.alpa_dp_solve_sweep(h, None, [2, 8])
+            B.alpa_dp_destroy(h)
+    cycle(3)
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    cycle(40)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 64 << 20                # no growth with the number of handles
