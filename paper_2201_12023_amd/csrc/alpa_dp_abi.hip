@@ -129,7 +129,8 @@ static int alloc_sweep_arrays(alpa_dp *h, int n_B)
     HIPCHK(hipMalloc(&h->d_sw_n, 2 * 4));
     HIPCHK(hipMalloc(&h->d_sw_state, n * sizeof(SolveState)));
     HIPCHK(hipMalloc(&h->d_sw_plans, n * sizeof(alpa_plan_t)));
-    if (h->fast_ok) {          // one slab of layers per B value; the general kernel reuses d_Fall
+    if (h->fast_ok && h->p.D <= 64) {   // one slab of layers per B value; the general kernel (also
+                                        // used above 64 devices) reuses d_Fall
         const size_t slab = (size_t)(h->p.Smax + 1) * (size_t)(h->p.K + 2) * (h->p.D + 1);
         HIPCHK(hipMalloc(&h->d_sw_Fall, n * slab * 4));
     }
@@ -238,7 +239,8 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
     h->generic_grid_max = gg;
     HIPCHK(hipMalloc(&h->d_scratch, (size_t)gg * 2 * LS * 4));
     // register/LDS kernel
-    h->fast_ok = K <= 64 && D <= 64;
+    h->fast_ok = K <= 64 && D <= 128;      // above 64 devices: one candidate per workgroup,
+                                           // the two-window form of the kernel
     if (h->fast_ok) {
         h->KP = 16 * ((K + 15) / 16);
         HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
@@ -494,7 +496,11 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             // enough candidates to fill the device twice over that way
             int nc = (bound >= 4 * h->fast_grid_max[2]) ? 2 : 1;
             if (const char *e = getenv("ALPA_DP_NC")) nc = atoi(e) == 2 ? 2 : 1;   // tuning aid
-            const int grid = std::max(1, std::min((bound + nc - 1) / nc, h->fast_grid_max[nc]));
+            const bool wide = p.D > 64;            // two windows of device counts, one candidate
+            if (wide) nc = 2;
+            const int per_wg = wide ? 1 : nc;
+            const int grid =
+                std::max(1, std::min((bound + per_wg - 1) / per_wg, h->fast_grid_max[nc]));
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
                         /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr, nullptr, h->d_gmin};
@@ -513,7 +519,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (n_B > 0) {
         HIPCHK(launch_sweep_epilogue(st, h->d_sw_B, n_B, &h->d_state->n_cand, h->d_cand, h->d_Fmin,
                                      h->d_Sbest, h->d_sw_state, prune_sel, h->d_sw_c, h->d_sw_s));
-        if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
+        if (h->fast_ok && p.D <= 64 && !(flags & ALPA_DP_GENERIC)) {
             const size_t slab = (size_t)(p.Smax + 1) * (size_t)(p.K + 2) * (p.D + 1);
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_sw_c, h->d_sw_n, h->d_sw_n + 1,
                         &h->d_state->wave_relax, nullptr, 0, 0, h->d_sw_FS,
@@ -542,7 +548,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         HIPCHK(launch_scatter_T(st, h->d_T, have_list ? h->d_rank : nullptr,
                                 have_list ? n_tmax : bound, h->d_state, d_out_T));
     // every layer of the winning candidate (does nothing if there is none), then the walk
-    if (h->fast_ok && !(flags & ALPA_DP_GENERIC)) {
+    if (h->fast_ok && p.D <= 64 && !(flags & ALPA_DP_GENERIC)) {
         FastArgs fa{p, h->d_recs, h->d_sizes, &h->d_state->best_c,
                     &h->d_state->plan_n, &h->d_state->plan_ticket, &h->d_state->wave_relax,
                     nullptr, 0, 0, h->d_tmpFS, h->d_tmpFS + 2, 1, h->d_Fall, &h->d_state->best_s,

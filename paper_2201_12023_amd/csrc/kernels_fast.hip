@@ -1,4 +1,5 @@
-// Register/LDS recurrence kernel for K <= 64 layers and N*M <= 64 devices (Eq. 3).
+// Register/LDS recurrence kernel for K <= 64 layers and N*M <= 64 devices (Eq. 3); up to 128
+// devices in a two-window form (see WIDE below).
 //
 // Mapping.  One workgroup evaluates one t_max candidate at a time (persistent workgroups
 // draw candidates from a ticket counter).  Lane l of every wave owns device count
@@ -210,7 +211,10 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // axis; NC = candidates evaluated together by one workgroup (they share every scalar load);
 // DUMP = also store every layer to F_all (plan recovery, NC = 1); COUNT = tally executed
 // half-blocks.  Fmin / Sbest have a spare slot at index dummy_idx for results nobody owns.
-template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
+// WIDE (with NC = 2): meshes of 65..128 devices.  One candidate per workgroup; the two
+// accumulator sets and the two LDS regions that otherwise belong to two candidates hold the
+// device counts 1..64 and 65..128 of the one candidate ("windows" 0 and 1).
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
 __global__ __launch_bounds__(WAVE * NWK * WI) __attribute__((amdgpu_waves_per_eu(4)))
 void recurrence_fast_kernel(
     Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g,
@@ -221,6 +225,8 @@ void recurrence_fast_kernel(
     const int32_t *__restrict__ group_min)
 {
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
+    static_assert(!WIDE || (NC == 2 && WI == 1 && !DUMP), "two windows use the two-candidate layout");
+    constexpr int NCAND = WIDE ? 1 : NC;               // candidates per workgroup
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
     constexpr int ROWS = KP + 6;                       // LDS rows per F layer (+ read-ahead slack)
@@ -243,14 +249,14 @@ void recurrence_fast_kernel(
     int32_t *Fnext = lds + NC * ROWS * WAVE;
     // candidate packing (two candidates, one pass): lane l works for candidate l / 32 on
     // device count d - 1 = pk_base + l % 32
-    constexpr bool PACK = NC == 2 && WI == 1 && !DUMP;
+    constexpr bool PACK = NC == 2 && WI == 1 && !DUMP && !WIDE;
     const int pk_base = max(0, D - 32);
     const int pk_dl = pk_base + (lane & 31);
     const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
     const bool half1 = lane >= 32;
     const int32_t size_of_lane = sizes[min(lane, S - 1)];   // lane q holds a_q (S <= 64)
     const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
-    const int n_groups = (n + NC - 1) / NC;
+    const int n_groups = (n + NCAND - 1) / NCAND;
     unsigned long long n_blocks_total = 0;
 
     for (;;) {
@@ -263,12 +269,12 @@ void recurrence_fast_kernel(
         const int tk = __builtin_amdgcn_readfirstlane(sh_tk[0]);
         __syncthreads();
         if (tk >= n_groups) break;                     // the workgroup's only exit
-        const int j0 = (descending ? (n_groups - 1 - tk) : tk) * NC;
-        int jj[NC];                                    // candidate indices (the last may repeat)
-        int32_t c[NC];
+        const int j0 = (descending ? (n_groups - 1 - tk) : tk) * NCAND;
+        int jj[NC];                                    // candidate indices (the last may repeat;
+        int32_t c[NC];                                 //  both windows serve one candidate)
 #pragma unroll
         for (int e = 0; e < NC; ++e) {
-            jj[e] = min(j0 + e, n - 1);
+            jj[e] = WIDE ? j0 : min(j0 + e, n - 1);
             c[e] = __builtin_amdgcn_readfirstlane(cand[jj[e]]);
         }
         if (prune) {
@@ -281,7 +287,7 @@ void recurrence_fast_kernel(
             __syncthreads();
             if (skip) {
 #pragma unroll
-                for (int e = 0; e < NC; ++e) {
+                for (int e = 0; e < NCAND; ++e) {
                     Fmin[jj[e]] = DEV_INF;             // all threads, same value
                     Sbest[jj[e]] = -1;
                 }
@@ -382,7 +388,8 @@ void recurrence_fast_kernel(
                 if (s == 1) {
                     // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
 #pragma unroll
-                    for (int e = 0; e < NC; ++e) G[e] = (lane + 1 == a) ? 0 : DEV_INF;
+                    for (int e = 0; e < NC; ++e)
+                        G[e] = ((WIDE ? WAVE * e : 0) + lane + 1 == a) ? 0 : DEV_INF;
                     int i = i0;
                     for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, ++i) {
                         load_half(hA, pA);
@@ -406,13 +413,20 @@ void recurrence_fast_kernel(
                     constexpr int NF = P ? 1 : NC;
                     const int dl = P ? pk_dl : lane;       // d - 1 served by this lane
                     const bool live = dl >= a;             // d - a_q >= 1
+                    // window 1 (WIDE): d - 1 = 64 + lane; its operand d - a_q lies in window 1
+                    // for lane >= a_q, else in window 0 at lane 64 + lane - a_q
+                    const bool live1 = WAVE + lane >= a;
+                    const int wide_delta = (lane >= a ? ROWS * WAVE + lane - a
+                                                      : max(0, WAVE + lane - a)) -
+                                           (live ? lane - a : 0);
                     auto row_ptr = [&](int i) {            // operand row of column i: row i + 1
                         return Fprev + (P ? pk_cand_off : 0) + (live ? dl - a : 0) + (i + 1) * WAVE;
                     };
                     struct Batch { HalfColumn X, Y; int32_t fX[NF], fY[NF]; } b0, b1;
                     auto operands = [&](const int32_t (&src)[NF]) {
 #pragma unroll
-                        for (int e = 0; e < NF; ++e) G[e] = live ? src[e] : DEV_INF;
+                        for (int e = 0; e < NF; ++e)
+                            G[e] = ((WIDE && e == 1) ? live1 : live) ? src[e] : DEV_INF;
                     };
                     auto relax = [&](int off, HalfColumn &h, int32_t mn) {
                         if constexpr (P)
@@ -425,7 +439,8 @@ void recurrence_fast_kernel(
                     auto single = [&](int off, cptr_t p, const int32_t *frow, int count, auto mnf) {
                         auto rows = [&](int32_t (&dst)[NF], int col) {
 #pragma unroll
-                            for (int e = 0; e < NF; ++e) dst[e] = frow[(e * ROWS + col) * WAVE];
+                            for (int e = 0; e < NF; ++e)
+                                dst[e] = frow[(WIDE && e == 1 ? wide_delta : e * ROWS * WAVE) + col * WAVE];
                         };
                         auto load2 = [&](Batch &b, int col) {
                             rows(b.fX, col);
@@ -486,7 +501,8 @@ void recurrence_fast_kernel(
                         const int32_t *frow = row_ptr(cAB);
                         auto load_AB = [&](Batch &b, int col) {
 #pragma unroll
-                            for (int e = 0; e < NF; ++e) b.fX[e] = frow[(e * ROWS + col) * WAVE];
+                            for (int e = 0; e < NF; ++e)
+                                b.fX[e] = frow[(WIDE && e == 1 ? wide_delta : e * ROWS * WAVE) + col * WAVE];
                             load_half(b.X, p1 + (size_t)col * STEP);
                             load_half(b.Y, p2 + (size_t)col * STEP);
                             fence_loads();
@@ -588,12 +604,14 @@ void recurrence_fast_kernel(
                 }
             }
         }
-        // lane D-1 holds F(s, first layer, all devices); wave 0 owns the results; a repeated
-        // last candidate goes to the spare slot
+        // lane D-1 (of window (D-1)/64) holds F(s, first layer, all devices); wave 0 owns the
+        // results; a repeated last candidate goes to the spare slot
 #pragma unroll
-        for (int e = 0; e < NC; ++e) {
-            const int32_t bestD = __builtin_amdgcn_readlane(best[e], D - 1);
-            const int32_t sD = __builtin_amdgcn_readlane(sbest[e], D - 1);
+        for (int e = 0; e < NCAND; ++e) {
+            const int32_t bv = (WIDE && D > WAVE) ? best[NC - 1] : best[e];
+            const int32_t sv = (WIDE && D > WAVE) ? sbest[NC - 1] : sbest[e];
+            const int32_t bestD = __builtin_amdgcn_readlane(bv, (D - 1) & (WAVE - 1));
+            const int32_t sD = __builtin_amdgcn_readlane(sv, (D - 1) & (WAVE - 1));
             const bool owner = (wid == 0) && (j0 + e < n);
             const int slot = owner ? jj[e] : dummy_idx;
             Fmin[slot] = bestD;                        // all lanes, same value
@@ -643,17 +661,17 @@ static size_t fast_lds_bytes()
     return (size_t)NC * (NWK * 16 + 6) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
 }
 
-template <int NWK, int WI, int NC, bool DUMP, bool COUNT>
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
 static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
 {
     const size_t lds = fast_lds_bytes<NWK, WI, NC>();
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(
-            (const void *)recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>,
+            (const void *)recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE>,
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT>), dim3(grid),
+    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE>), dim3(grid),
                        dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
                        a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
                        a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p, a.group_min);
@@ -666,15 +684,18 @@ static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc
     switch (mode) {
     case FAST_MODE_PLAN: return launch_one<NWK, PLAN_WI, 1, true, false>(st, a, grid);
     case FAST_MODE_COUNT:
+        if (a.p.D > WAVE) return launch_one<NWK, 1, 2, false, true, true>(st, a, grid);
         return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
                        : launch_one<NWK, 1, 1, false, true>(st, a, grid);
     default:
+        if (a.p.D > WAVE) return launch_one<NWK, 1, 2, false, false, true>(st, a, grid);
         return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
                        : launch_one<NWK, 1, 1, false, false>(st, a, grid);
     }
 }
 
-// nc = candidates per workgroup (1 or 2); grid = persistent workgroups
+// nc = candidates per workgroup (1 or 2; meshes of more than 64 devices: always one, in the
+// two-window form); grid = persistent workgroups
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid)
 {
     switch ((a.p.K + 15) / 16) {

@@ -390,3 +390,34 @@ def test_create_and_destroy_give_the_memory_back():
     torch.cuda.synchronize()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < 64 << 20                # no growth with the number of handles
+
+
+WIDE_CASES = [  # seed, K, N, M: 65..128 devices, K <= 64: the two-window form of the fast kernel
+    (60, 40, 10, 8), (61, 64, 16, 8), (62, 33, 9, 8), (63, 20, 3, 32), (64, 57, 2, 64),
+    (65, 12, 33, 2), (66, 64, 13, 8), (67, 5, 4, 32),
+]
+
+
+@pytest.mark.parametrize("kernel", list(KERNELS))
+@pytest.mark.parametrize("case", WIDE_CASES, ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_meshes_of_65_to_128_devices(case, kernel):
+    seed, K, N, M = case
+    rng = np.random.default_rng(seed)
+    w = W.random_problem(seed, K, N, M, inf_frac=float(rng.choice([0.0, 0.2, 0.5])),
+                         value_hi=int(rng.choice([6, 60, 6000])))
+    cand_ref = oracle.all_candidates(w.table, w.shapes)
+    if len(cand_ref) > 150:
+        cand_ref = oracle.quantiles(cand_ref, 150)
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            flags = KERNELS[kernel] | (B.ALPA_DP_PRUNE if prune else 0)
+            T, plan = B.alpa_dp_solve(h, cand_ref, flags=flags)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+            if not prune:
+                plans = B.alpa_dp_solve_sweep(h, cand_ref, [1, w.B, 50], flags=flags)
+                _same_plan(plans[1], p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
