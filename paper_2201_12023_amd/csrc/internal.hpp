@@ -148,7 +148,7 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      const int32_t *sizes, const int32_t *cand,
                                      const int32_t *n_cand_p, int32_t *ticket, int64_t *chunk_min,
                                      int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
-                                     int n_layers, int grid);
+                                     int n_layers, int grid, const int32_t *s_top_p = nullptr);
 struct FastArgs {
     Problem p;
     const int32_t *recs, *sizes, *cand, *n_cand_p;

@@ -12,9 +12,13 @@ namespace alpa {
 // F(s, k, d) of Eq. 3 for one candidate c, with F layers of (K+2) x (D+1) int32 each
 // (k = 0..K+1, layers 1-based, k = K+1 is the "past the end" row; d = 0..D).
 // layer(s) = slot + (s % n_layers) * layer_size.
+// band (plan recovery of a winner with s_top stages): only layers up to s_top are filled, and
+// of layer s only first layers k >= s_top - s + 1, the cells the walk back from (s_top, first
+// layer 1) can reach; the others keep +infinity.
 __device__ void fill_layers(const Problem &p, const int32_t *__restrict__ table,
                             const int32_t *__restrict__ sizes, int32_t c, int32_t *slot,
-                            int n_layers, int32_t *best_out, int32_t *sbest_out)
+                            int n_layers, int s_top, bool band, int32_t *best_out,
+                            int32_t *sbest_out)
 {
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
@@ -23,7 +27,7 @@ __device__ void fill_layers(const Problem &p, const int32_t *__restrict__ table,
     for (int x = tid; x < LS; x += nt) slot[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
     __syncthreads();
     int32_t best = DEV_INF, sbest = 0;
-    for (int s = 1; s <= p.Smax; ++s) {
+    for (int s = 1; s <= s_top; ++s) {
         const int32_t *prev = slot + (size_t)((s - 1) % n_layers) * LS;
         int32_t *cur = slot + (size_t)(s % n_layers) * LS;
         const int32_t *tab_s = table + (size_t)(s - 1) * K * K * S;
@@ -33,7 +37,7 @@ __device__ void fill_layers(const Problem &p, const int32_t *__restrict__ table,
             // s stages need s layers and s devices: cells with k > K - s + 1 or d < s stay
             // infinite, and an operand F(s-1, i+1, .) can only be finite for K - i >= s - 1
             // (for s = 1 only the "past the end" row i + 1 = K + 1 is)
-            if (k >= 1 && k <= K - s + 1 && d >= s) {
+            if (k >= (band ? max(1, s_top - s + 1) : 1) && k <= K - s + 1 && d >= s) {
                 const int i_first = (s == 1) ? K : k, i_last = K - s + 1;
                 for (int i = i_first; i <= i_last; ++i) {
                     const int32_t *tp = tab_s + ((size_t)(k - 1) * K + (i - 1)) * S;
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(GENERIC_MAX_THREADS) void recurrence_generic_kernel
     Problem p, const int32_t *__restrict__ table, const int32_t *__restrict__ sizes,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
     int64_t *chunk_min, int prune, int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest,
-    int32_t *scratch, int n_layers)
+    int32_t *scratch, int n_layers, const int32_t *__restrict__ s_top_p)
 {
     __shared__ int32_t sh_tk[GENERIC_MAX_THREADS];
     __shared__ int sh_skip[WAVE];
@@ -113,7 +117,8 @@ __global__ __launch_bounds__(GENERIC_MAX_THREADS) void recurrence_generic_kernel
             }
         }
         int32_t best, sbest;
-        fill_layers(p, table, sizes, c, slot, n_layers, &best, &sbest);
+        const int s_top = s_top_p ? min(p.Smax, *s_top_p) : p.Smax;
+        fill_layers(p, table, sizes, c, slot, n_layers, s_top, s_top_p != nullptr, &best, &sbest);
         Fmin[j] = best;                           // all threads, same value
         Sbest[j] = best >= DEV_INF ? 0 : sbest;
         if (prune && best < DEV_INF)              // uniform; the minimum is idempotent
@@ -391,12 +396,13 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      const int32_t *sizes, const int32_t *cand,
                                      const int32_t *n_cand_p, int32_t *ticket, int64_t *chunk_min,
                                      int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
-                                     int n_layers, int grid)
+                                     int n_layers, int grid, const int32_t *s_top_p)
 {
     // a lone workgroup (the plan-recovery run of one candidate) gets the widest block
     const int threads = grid == 1 ? GENERIC_MAX_THREADS : 256;
     hipLaunchKernelGGL(recurrence_generic_kernel, dim3(grid), dim3(threads), 0, st, p, table, sizes,
-                       cand, n_cand_p, ticket, chunk_min, prune, Fmin, Sbest, scratch, n_layers);
+                       cand, n_cand_p, ticket, chunk_min, prune, Fmin, Sbest, scratch, n_layers,
+                       s_top_p);
     return hipGetLastError();
 }
 
