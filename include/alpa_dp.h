@@ -52,7 +52,7 @@ extern "C" {
 #define ALPA_DP_PRUNE         1u          /* early pruning of Alg. 1 / Sec. 5.2 opt. #1 */
 #define ALPA_DP_COUNT_WORK    4u          /* tally executed work (alpa_dp_last_counters) */
 #define ALPA_DP_GENERIC       2u          /* use the general kernel even where the
-                                             K <= 64, N*M <= 64 kernel applies   */
+                                             register/LDS kernel applies         */
 
 typedef struct alpa_dp alpa_dp_t;         /* opaque, owned by the library        */
 
@@ -200,7 +200,7 @@ int alpa_dp_solve_dev(alpa_dp_t *h, const int32_t *d_tmax, int n_tmax, unsigned 
  *
  * The handle's own B and the running best of alpa_dp_best() are not touched.  Blocking.
  * On the first call (and when n_B grows) device memory for n_B sets of layers is
- * allocated: n_B * (min(K, N*M) + 1) * (K + 2) * (N*M + 1) * 4 bytes when K <= 64 and
+ * allocated: n_B * (min(K, N*M) + 1) * (K + 2) * (N*M + 1) * 4 bytes when K <= 128 and
  * N*M <= 64.  Errors: EINVAL (null pointers, n_B or a B value out of range, and the
  * candidate-list errors of alpa_dp_solve), ENOMEM, EHIP.
  */

@@ -239,8 +239,9 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
     h->generic_grid_max = gg;
     HIPCHK(hipMalloc(&h->d_scratch, (size_t)gg * 2 * LS * 4));
     // register/LDS kernel
-    h->fast_ok = K <= 64 && D <= 128;      // above 64 devices: one candidate per workgroup,
-                                           // the two-window form of the kernel
+    // up to 128 layers on up to 64 devices; above 64 devices (one candidate per workgroup, the
+    // two-window form of the kernel) up to 64 layers
+    h->fast_ok = (K <= 128 && D <= 64) || (K <= 64 && D <= 128);
     if (h->fast_ok) {
         h->KP = 16 * ((K + 15) / 16);
         HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));

@@ -1,0 +1,650 @@
+// Register/LDS recurrence kernel (Eq. 3) for K <= 128 layers on N*M <= 64 devices, and for
+// K <= 64 layers on up to 128 devices in a two-window form (see WIDE below).
+//
+// Mapping.  One workgroup evaluates one t_max candidate at a time (persistent workgroups
+// draw candidates from a ticket counter).  Lane l of every wave owns device count
+// d = l + 1.  The first layers k are cut into half-blocks of 8; a workgroup has NWK =
+// ceil(K / 16) waves along that axis and wave w owns half-blocks w ("A") and 2*NWK-1-w
+// ("B"): the triangular work (a column with last layer i only touches first layers <= i)
+// is then the same for every wave.  The 16 accumulators F(s, k, .) of a wave live in VGPRs;
+// with WI > 1 the submesh shapes q are dealt round-robin over WI wave groups and the
+// partial minima are merged through LDS.  The previous layer F(s-1, ., .) lives in LDS, one
+// row of 64 lanes per first layer.  For a fixed (last layer i, shape q) the operand
+// F(s-1, i+1, d - a_q) is one lane-shifted LDS row read, reused for all first layers of the
+// wave, and t_intra(k..i, q, s) is the same for all lanes: it is fetched with scalar loads
+// and used as the scalar operand of the add, so a cell-update costs one v_add and one v_min.
+// The filter t_intra <= t_max is wave-uniform; it is resolved per half-block from its
+// precomputed min / max (skip, take unfiltered, or select per entry on the scalar unit).
+// Infinite entries need no filter: DEV_INF + anything >= DEV_INF and accumulators start at
+// DEV_INF.  Column loads (scalars and the LDS row) are issued one column ahead.
+//
+// Table layout (built once per handle by repack_fast_kernel): one record per column
+// (s-1, q, i), columns in that order (i fastest); a record is KP/8 half-block entries of
+// HB_INTS = 10 int32 (KP = 16 * ceil(K/16)):
+//   {min, max over the finite t_intra of first layers 8hb..8hb+7 and last layer i
+//    ({DEV_INF, DEV_INF} if there is none), then the 8 values themselves: DEV_INF where the
+//    first layer is > i or >= K or the entry is +infinity}.
+// The array is padded by a few records so that the one-column-ahead loads may run past the
+// last column.
+#include "internal.hpp"
+#pragma once
+#include "internal.hpp"
+
+#include <type_traits>
+
+namespace alpa {
+
+typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-load path
+
+constexpr int HB_INTS = 10;
+constexpr int END_SHAPES = 12;         // shapes covered by the early-stop table (3 registers)
+
+// Early-stop table: 8 groups of GW columns per (shape, half-block); GW = 8 up to 64 layers.
+constexpr int END_GROUPS = 8;
+constexpr int end_group_cols(int KP) { return KP > 64 ? KP / 8 : 8; }
+
+// One half-block's share of a column, loaded one step ahead of its use.
+struct HalfColumn {
+    int32_t t[8];              // t_intra for 8 first layers (scalar registers)
+    int32_t mn, mx;            // the half-block's min / max over finite entries
+};
+
+__device__ __forceinline__ void load_half(HalfColumn &h, cptr_t rec)
+{
+    h.mn = rec[0];
+    h.mx = rec[1];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) h.t[u] = rec[2 + u];
+}
+
+// Makes loaded values "used" here, so that the wait for them is placed before the next
+// loads are issued (scalar loads return out of order: any later wait would also wait for
+// the loads just issued).  The memory clobber keeps later loads below this point.
+__device__ __forceinline__ void settle(const HalfColumn &h)
+{
+    asm volatile("" :: "s"(h.t[0]), "s"(h.t[1]), "s"(h.t[2]), "s"(h.t[3]), "s"(h.t[4]),
+                       "s"(h.t[5]), "s"(h.t[6]), "s"(h.t[7]), "s"(h.mn), "s"(h.mx)
+                 : "memory");
+}
+__device__ __forceinline__ void settle(const HalfColumn &h, int32_t f)
+{
+    asm volatile("" :: "s"(h.t[0]), "s"(h.t[1]), "s"(h.t[2]), "s"(h.t[3]), "s"(h.t[4]),
+                       "s"(h.t[5]), "s"(h.t[6]), "s"(h.t[7]), "s"(h.mn), "s"(h.mx), "v"(f)
+                 : "memory");
+}
+__device__ __forceinline__ void fence_loads() { asm volatile("" ::: "memory"); }
+
+// Eight first layers against one column, for the NC candidates of the workgroup (ascending:
+// c[0] <= c[1] <= ...).  A half-block is skipped when none of its entries passes the largest
+// candidate, taken unfiltered when every finite entry passes the smallest, else filtered on
+// the scalar unit candidate by candidate, from the largest down (the filtered set only
+// shrinks, so the filter is applied in place).
+template <int NC, bool COUNT>
+__device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)[8], int32_t mn,
+                                       int32_t mx, const int32_t (&G)[NC], const int32_t (&c)[NC],
+                                       unsigned &n_blocks)
+{
+    if (mn <= c[NC - 1]) {                    // else nothing passes even the largest candidate
+#pragma unroll
+        for (int e = NC - 1; e >= 0; --e) {   // largest candidate first: the filter only shrinks
+            if (mx > c[e]) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[e]) ? t[u] : DEV_INF;
+            }
+            if (COUNT) ++n_blocks;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[e][off + u] = min(acc[e][off + u], t[u] + G[e]);
+            // The next candidate filters the same eight registers in place; pinning them here
+            // keeps the two update sequences apart (merged, they need a second copy of the
+            // values, i.e. eight scalar moves per half-block).
+            if (e > 0)
+                asm volatile("" : "+s"(t[0]), "+s"(t[1]), "+s"(t[2]), "+s"(t[3]), "+s"(t[4]),
+                                  "+s"(t[5]), "+s"(t[6]), "+s"(t[7]), "+v"(acc[e][off + 0]),
+                                  "+v"(acc[e][off + 1]), "+v"(acc[e][off + 2]),
+                                  "+v"(acc[e][off + 3]), "+v"(acc[e][off + 4]),
+                                  "+v"(acc[e][off + 5]), "+v"(acc[e][off + 6]),
+                                  "+v"(acc[e][off + 7]));
+        }
+    }
+}
+
+// Two candidates in one pass.  Where every device count a shape can still serve at this layer
+// lies in one window of 32 (d - 1 in [base, base + 32)), lanes 0..31 work for candidate 0 and
+// lanes 32..63 for candidate 1, both on that window: the scalar t_intra values are the same
+// for both, so one add + min per first layer serves the two of them.  GP is the packed operand
+// (lane l: F(s-1, i+1, d - a_q) of candidate l / 32), accP the packed accumulators.  If every
+// finite entry passes both candidates one update does it; otherwise each candidate gets its
+// own filtered update with the other half's operand set to infinity.
+template <bool COUNT>
+__device__ __forceinline__ void relax8p(int32_t (&accP)[16], int off, int32_t (&t)[8], int32_t mn,
+                                        int32_t mx, int32_t GP, const int32_t (&c)[2], bool half1,
+                                        unsigned &n_blocks)
+{
+    if (mn <= c[1]) {                         // else nothing passes even the larger candidate
+        const bool both = mx <= c[0];
+        if (mx > c[1]) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[1]) ? t[u] : DEV_INF;
+        }
+        const int32_t G1 = (both || half1) ? GP : DEV_INF;
+        if (COUNT) ++n_blocks;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) accP[off + u] = min(accP[off + u], t[u] + G1);
+        if (!both) {
+            asm volatile("" : "+s"(t[0]), "+s"(t[1]), "+s"(t[2]), "+s"(t[3]), "+s"(t[4]),
+                              "+s"(t[5]), "+s"(t[6]), "+s"(t[7]), "+v"(accP[off + 0]),
+                              "+v"(accP[off + 1]), "+v"(accP[off + 2]), "+v"(accP[off + 3]),
+                              "+v"(accP[off + 4]), "+v"(accP[off + 5]), "+v"(accP[off + 6]),
+                              "+v"(accP[off + 7]));
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[0]) ? t[u] : DEV_INF;
+            const int32_t G0 = half1 ? DEV_INF : GP;
+            if (COUNT) ++n_blocks;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) accP[off + u] = min(accP[off + u], t[u] + G0);
+        }
+    }
+}
+
+// Lower-index evidence for the pruning rule (see recurrence_generic_kernel).
+__device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, int32_t c, int B,
+                                              int lane)
+{
+    const int g = j / PRUNE_CHUNK;
+    int64_t m = INF_I64;
+    for (int x = lane; x < g; x += WAVE)
+        m = min64(m, __atomic_load_n(&chunk_min[x], __ATOMIC_RELAXED));
+    m = wave_min_i64(m);
+    return m != INF_I64 && (int64_t)B * (int64_t)c >= m;
+}
+
+// NWK = waves along the first-layer axis (= ceil(K / 16)); WI = wave groups along the shape
+// axis; NC = candidates evaluated together by one workgroup (they share every scalar load);
+// DUMP = also store every layer to F_all (plan recovery, NC = 1); COUNT = tally executed
+// half-blocks.  Fmin / Sbest have a spare slot at index dummy_idx for results nobody owns.
+// WIDE (with NC = 2): meshes of 65..128 devices.  One candidate per workgroup; the two
+// accumulator sets and the two LDS regions that otherwise belong to two candidates hold the
+// device counts 1..64 and 65..128 of the one candidate ("windows" 0 and 1).
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
+__global__ __launch_bounds__(WAVE * NWK * WI) __attribute__((amdgpu_waves_per_eu(4)))
+void recurrence_fast_kernel(
+    Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g,
+    const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
+    unsigned long long *wave_relax, int64_t *chunk_min, int prune, int descending,
+    int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest, int dummy_idx,
+    int32_t *__restrict__ F_all, const int32_t *__restrict__ s_top_p,
+    const int32_t *__restrict__ group_min)
+{
+    static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
+    static_assert(!WIDE || (NC == 2 && WI == 1 && !DUMP), "two windows use the two-candidate layout");
+    constexpr int NCAND = WIDE ? 1 : NC;               // candidates per workgroup
+    constexpr int NT = WAVE * NWK * WI;
+    constexpr int KP = NWK * 16;
+    constexpr int ROWS = KP + 6;                       // LDS rows per F layer (+ read-ahead slack)
+    extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
+    __shared__ int32_t sh_tk[NT];
+    __shared__ int32_t sh_skip[NWK * WI];
+    __shared__ int32_t sh_ends[NWK * WI * (END_SHAPES / 4) * WAVE];   // early-stop table
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wk = wid % NWK, wi = wid / NWK;
+    const int hbA = wk, hbB = 2 * NWK - 1 - wk;        // the wave's two half-blocks of 8 first layers
+    const int rowA = 8 * hbA, rowB = 8 * hbB;
+    const int K = p.K, D = p.D, S = p.S;
+    const int LS = (K + 2) * (D + 1);
+    constexpr int REC = (KP / 8) * HB_INTS;            // int32 per column record
+    constexpr int GW = end_group_cols(KP);             // columns per early-stop group
+    const cptr_t recs = (cptr_t)recs_g;
+    const cptr_t sizes = (cptr_t)sizes_g;
+    int32_t *Fprev = lds;
+    int32_t *Fnext = lds + NC * ROWS * WAVE;
+    // candidate packing (two candidates, one pass): lane l works for candidate l / 32 on
+    // device count d - 1 = pk_base + l % 32
+    constexpr bool PACK = NC == 2 && WI == 1 && !DUMP && !WIDE;
+    const int pk_base = max(0, D - 32);
+    const int pk_dl = pk_base + (lane & 31);
+    const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
+    const bool half1 = lane >= 32;
+    const int32_t size_of_lane = sizes[min(lane, S - 1)];   // lane q holds a_q (S <= 64)
+    const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
+    const int n_groups = (n + NCAND - 1) / NCAND;
+    unsigned long long n_blocks_total = 0;
+
+    for (;;) {
+        // Every thread issues the atomic (thread 0 adds 1, the others 0) and all read thread
+        // 0's return value.  No branch on the thread id may appear in this loop: it would be
+        // loop-invariant, the compiler splits the loop on it, and the lanes of one wave then
+        // run the persistent loop out of step with each other.
+        sh_tk[tid] = atomicAdd(ticket, tid == 0 ? 1 : 0);
+        __syncthreads();
+        const int tk = __builtin_amdgcn_readfirstlane(sh_tk[0]);
+        __syncthreads();
+        if (tk >= n_groups) break;                     // the workgroup's only exit
+        const int j0 = (descending ? (n_groups - 1 - tk) : tk) * NCAND;
+        int jj[NC];                                    // candidate indices (the last may repeat;
+        int32_t c[NC];                                 //  both windows serve one candidate)
+#pragma unroll
+        for (int e = 0; e < NC; ++e) {
+            jj[e] = WIDE ? j0 : min(j0 + e, n - 1);
+            c[e] = __builtin_amdgcn_readfirstlane(cand[jj[e]]);
+        }
+        if (prune) {
+            // If the lowest candidate of the group may be skipped so may the others (their
+            // evidence set is a superset and B * t_max is larger).  Wave 0's reading of the
+            // published minima decides for the whole workgroup.
+            sh_skip[wid] = can_skip_fast(chunk_min, jj[0], c[0], p.B, lane) ? 1 : 0;
+            __syncthreads();
+            const int skip = __builtin_amdgcn_readfirstlane(sh_skip[0]);
+            __syncthreads();
+            if (skip) {
+#pragma unroll
+                for (int e = 0; e < NCAND; ++e) {
+                    Fmin[jj[e]] = DEV_INF;             // all threads, same value
+                    Sbest[jj[e]] = -1;
+                }
+                continue;
+            }
+        }
+        // Plan recovery walks back from F(s*, first layer 1, all devices): only layers up to
+        // s* are needed, and of layer s only first layers (0-based) >= s* - s, since each of
+        // the s* - s stages in front takes at least one layer.
+        const int s_top =
+            DUMP ? min(p.Smax, __builtin_amdgcn_readfirstlane(s_top_p[jj[0]])) : p.Smax;
+        int32_t *F_out = DUMP ? F_all + (size_t)jj[0] * (size_t)(p.Smax + 1) * LS : nullptr;
+        if (DUMP) {
+            const int total = (s_top + 1) * LS;
+            for (int x = tid; x < total; x += NT) F_out[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
+            __syncthreads();
+        }
+        // Where the column loops may stop: lane s - 1 gets, for every shape q and the wave's two
+        // half-blocks, the number of leading 8-column groups in which the largest candidate
+        // still finds an entry (4 bits each, shape q at bits 8 (q % 4) of word q / 4 of the
+        // wave's rows in sh_ends; only the wave itself reads them, so no barrier is needed).
+        // Shapes beyond END_SHAPES are not covered (their loops run to the end).
+        {
+            const int32_t cmax = c[NC - 1];
+            constexpr int NHB = KP / 8;
+            int32_t word = 0;
+#pragma nounroll
+            for (int q = 0; q < END_SHAPES; ++q) {     // rows of shapes >= S are never read
+                if (q < S) {
+                    const int32_t *gA = group_min + ((q * NHB + hbA) * END_GROUPS) * WAVE + lane;
+                    const int32_t *gB = group_min + ((q * NHB + hbB) * END_GROUPS) * WAVE + lane;
+                    int nA = 0, nB = 0;
+#pragma unroll
+                    for (int j = 0; j < END_GROUPS; ++j) {
+                        nA += gA[j * WAVE] <= cmax ? 1 : 0;
+                        nB += gB[j * WAVE] <= cmax ? 1 : 0;
+                    }
+                    word |= (nA | (nB << 4)) << (8 * (q & 3));
+                }
+                if ((q & 3) == 3) {                    // four shapes per word
+                    sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + lane] = word;
+                    word = 0;
+                }
+            }
+        }
+        int32_t best[NC], sbest[NC];
+#pragma unroll
+        for (int e = 0; e < NC; ++e) { best[e] = DEV_INF; sbest[e] = 0; }
+        unsigned n_blocks = 0;
+        for (int s = 1; s <= s_top; ++s) {
+            const bool needA = !DUMP || rowA + 7 >= s_top - s;
+            const bool needB = !DUMP || rowB + 7 >= s_top - s;
+            auto mnA = [&](const HalfColumn &h) { return needA ? h.mn : DEV_INF; };   // "no entry
+            auto mnB = [&](const HalfColumn &h) { return needB ? h.mn : DEV_INF; };   //  passes"
+            int32_t acc[NC][16];                       // [0..7] half-block A, [8..15] half-block B
+#pragma unroll
+            for (int e = 0; e < NC; ++e)
+#pragma unroll
+                for (int u = 0; u < 16; ++u) acc[e][u] = DEV_INF;
+            int32_t accP[16];                          // packed passes (PACK only)
+#pragma unroll
+            for (int u = 0; u < 16; ++u) accP[u] = DEV_INF;
+            int32_t c2[2] = {c[0], c[NC - 1]};
+            const int i_lo = (s == 1) ? K - 1 : 0;     // 0-based last layer
+            const int i_hi = K - s;                    // at least s-1 layers must remain
+            const int i0 = max(i_lo, rowA);            // columns that reach half-block A
+            if (WI > 1) {
+                for (int x = tid; x < NC * ROWS * WAVE; x += NT) Fnext[x] = DEV_INF;
+            }
+            bool packed_any = false;                   // a packed pass touched accP
+            // Two passes over the shapes: first those whose updates go candidate by candidate,
+            // then those served by the packed form (one pass at a time keeps each loop's set
+            // of live accumulators, and with it the register traffic between them, small).
+            auto shapes_pass = [&](auto PASS_PACKED) {
+            constexpr bool PASS_P = decltype(PASS_PACKED)::value;
+            for (int q = wi; q < S; q += WI) {          // wave group wi takes every WI-th shape
+                const int a = __builtin_amdgcn_readlane(size_of_lane, q);
+                if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
+                if (i0 > i_hi) continue;
+                // packed when every device count the shape can still serve is in the window
+                if ((PACK && s > 1 && a + s - 2 >= pk_base) != PASS_P) continue;
+                // first column group without anything for the largest candidate, per half-block
+                int endA = K, endB = K;
+                if (q < END_SHAPES) {
+                    const int bits = __builtin_amdgcn_readfirstlane(
+                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + s - 1]) >> (8 * (q & 3));
+                    endA = needA ? GW * (bits & 15) : 0;
+                    endB = needB ? GW * ((bits >> 4) & 15) : 0;
+                }
+                if (s > 1 && endA <= i0 && endB <= rowB) continue;   // nothing alive in reach
+                if (PASS_P) packed_any = true;
+                constexpr int STEP = REC;
+                const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
+                cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
+                const int ncol = i_hi - i0 + 1;                // columns of this wave
+                HalfColumn hA, hB;
+                int32_t G[NC];
+                if (s == 1) {
+                    // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
+#pragma unroll
+                    for (int e = 0; e < NC; ++e)
+                        G[e] = ((WIDE ? WAVE * e : 0) + lane + 1 == a) ? 0 : DEV_INF;
+                    int i = i0;
+                    for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, ++i) {
+                        load_half(hA, pA);
+                        load_half(hB, pB);
+                        relax8<NC, COUNT>(acc, 0, hA.t, mnA(hA), hA.mx, G, c, n_blocks);
+                        if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, mnB(hB), hB.mx, G, c, n_blocks);
+                    }
+                    continue;
+                }
+                auto columns = [&](auto PK) {
+                    // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
+                    // their LDS rows; while one batch is computed the loads of the next are in
+                    // flight, so every wait is covered by a whole batch of updates.  Three
+                    // phases: columns that reach only half-block A (a batch = the A halves of two
+                    // columns), columns in which both half-blocks still have entries for the
+                    // largest candidate (a batch = the A and B halves of one column), and the
+                    // columns in which only half-block B has (a batch = the B halves of two
+                    // columns).  Loads past the last column land in the padding and are dropped.
+                    // P: the two candidates share each pass (see relax8p); one LDS row per column
+                    constexpr bool P = decltype(PK)::value;
+                    constexpr int NF = P ? 1 : NC;
+                    const int dl = P ? pk_dl : lane;       // d - 1 served by this lane
+                    const bool live = dl >= a;             // d - a_q >= 1
+                    // window 1 (WIDE): d - 1 = 64 + lane; its operand d - a_q lies in window 1
+                    // for lane >= a_q, else in window 0 at lane 64 + lane - a_q
+                    const bool live1 = WAVE + lane >= a;
+                    const int wide_delta = (lane >= a ? ROWS * WAVE + lane - a
+                                                      : max(0, WAVE + lane - a)) -
+                                           (live ? lane - a : 0);
+                    auto row_ptr = [&](int i) {            // operand row of column i: row i + 1
+                        return Fprev + (P ? pk_cand_off : 0) + (live ? dl - a : 0) + (i + 1) * WAVE;
+                    };
+                    struct Batch { HalfColumn X, Y; int32_t fX[NF], fY[NF]; } b0, b1;
+                    auto operands = [&](const int32_t (&src)[NF]) {
+#pragma unroll
+                        for (int e = 0; e < NF; ++e)
+                            G[e] = ((WIDE && e == 1) ? live1 : live) ? src[e] : DEV_INF;
+                    };
+                    auto relax = [&](int off, HalfColumn &h, int32_t mn) {
+                        if constexpr (P)
+                            relax8p<COUNT>(accP, off, h.t, mn, h.mx, G[0], c2, half1, n_blocks);
+                        else
+                            relax8<NC, COUNT>(acc, off, h.t, mn, h.mx, G, c, n_blocks);
+                    };
+                    // `count` columns from the one p / frow point at, one half-block (acc rows
+                    // off..off+7) only
+                    auto single = [&](int off, cptr_t p, const int32_t *frow, int count, auto mnf) {
+                        auto rows = [&](int32_t (&dst)[NF], int col) {
+#pragma unroll
+                            for (int e = 0; e < NF; ++e)
+                                dst[e] = frow[(WIDE && e == 1 ? wide_delta : e * ROWS * WAVE) + col * WAVE];
+                        };
+                        auto load2 = [&](Batch &b, int col) {
+                            rows(b.fX, col);
+                            rows(b.fY, col + 1);
+                            load_half(b.X, p + (size_t)col * STEP);
+                            load_half(b.Y, p + (size_t)(col + 1) * STEP);
+                            fence_loads();
+                        };
+                        auto compute2 = [&](Batch &b) {
+                            operands(b.fX);
+                            relax(off, b.X, mnf(b.X));
+                            operands(b.fY);
+                            relax(off, b.Y, mnf(b.Y));
+                        };
+                        auto settle2 = [&](const Batch &b) {
+                            settle(b.X, b.fX[0]);
+                            settle(b.Y, b.fY[0]);
+                        };
+                        int left = count;
+                        if (left >= 2) {
+                            load2(b0, 0);
+                            for (; left >= 4; left -= 4) {
+                                settle2(b0);
+                                load2(b1, 2);
+                                compute2(b0);
+                                settle2(b1);
+                                load2(b0, 4);
+                                compute2(b1);
+                                p += 4 * STEP;
+                                frow += 4 * WAVE;
+                            }
+                            if (left >= 2) {
+                                settle2(b0);
+                                compute2(b0);
+                                p += 2 * STEP;
+                                frow += 2 * WAVE;
+                                left -= 2;
+                            }
+                        }
+                        if (left == 1) {
+                            rows(b0.fX, 0);
+                            load_half(b0.X, p);
+                            operands(b0.fX);
+                            relax(off, b0.X, mnf(b0.X));
+                        }
+                    };
+                    // columns of each phase; endA / endB bound where the half-blocks still
+                    // have something for the largest candidate
+                    const int n1 = max(0, min(rowB - i0, ncol));       // reach half-block A only
+                    const int cAB = i0 + n1;                           // first column reaching B
+                    const int stopAB = endA > endB ? endA : min(endA, endB);
+                    const int nAB = max(0, min(ncol - n1, stopAB - cAB));
+                    const int cB = cAB + nAB;                          // B alone from here
+                    const int nB = max(0, min(i_hi + 1, endB) - cB);
+                    single(0, pA, row_ptr(i0), max(0, min(n1, endA - i0)), mnA);
+                    {
+                        cptr_t p1 = pA + (size_t)n1 * STEP, p2 = pB + (size_t)n1 * STEP;
+                        const int32_t *frow = row_ptr(cAB);
+                        auto load_AB = [&](Batch &b, int col) {
+#pragma unroll
+                            for (int e = 0; e < NF; ++e)
+                                b.fX[e] = frow[(WIDE && e == 1 ? wide_delta : e * ROWS * WAVE) + col * WAVE];
+                            load_half(b.X, p1 + (size_t)col * STEP);
+                            load_half(b.Y, p2 + (size_t)col * STEP);
+                            fence_loads();
+                        };
+                        auto compute_AB = [&](Batch &b) {
+                            operands(b.fX);
+                            relax(0, b.X, mnA(b.X));
+                            relax(8, b.Y, mnB(b.Y));
+                        };
+                        auto settle_AB = [&](const Batch &b) {
+                            settle(b.X, b.fX[0]);
+                            settle(b.Y);
+                        };
+                        int left = nAB;
+                        if (left >= 1) {
+                            load_AB(b0, 0);
+                            for (; left >= 2; left -= 2) {
+                                settle_AB(b0);
+                                load_AB(b1, 1);
+                                compute_AB(b0);
+                                settle_AB(b1);
+                                load_AB(b0, 2);
+                                compute_AB(b1);
+                                p1 += 2 * STEP;
+                                p2 += 2 * STEP;
+                                frow += 2 * WAVE;
+                            }
+                            if (left == 1) {
+                                settle_AB(b0);
+                                compute_AB(b0);
+                            }
+                        }
+                    }
+                    single(8, pB + (size_t)(cB - i0) * STEP, row_ptr(cB), nB, mnB);
+                };
+                columns(PASS_PACKED);
+            }
+            };
+            shapes_pass(std::false_type{});
+            if constexpr (PACK) shapes_pass(std::true_type{});
+            if (PACK && packed_any) {
+                // lane l (d - 1 = l) takes candidate e's packed result from lane 32 e + l - pk_base
+                const int rel = lane - pk_base;
+                const bool in_window = rel >= 0 && rel < 32;
+#pragma unroll
+                for (int e = 0; e < NC; ++e)
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const int32_t v = __shfl(accP[u], (32 * e + rel) & 63, 64);
+                        acc[e][u] = min(acc[e][u], in_window ? v : DEV_INF);
+                    }
+            }
+            __syncthreads();                           // every wave is done reading Fprev
+            int32_t f1[NC];
+            if (WI == 1) {
+#pragma unroll
+                for (int e = 0; e < NC; ++e)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {      // rows 0 and >= K are never operands
+                        Fprev[(e * ROWS + rowA + u) * WAVE + lane] = acc[e][u];
+                        Fprev[(e * ROWS + rowB + u) * WAVE + lane] = acc[e][8 + u];
+                    }
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < NC; ++e) f1[e] = acc[e][0];   // F(s, first layer, .) in wave 0
+            } else {
+#pragma unroll
+                for (int e = 0; e < NC; ++e)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        atomicMin(&Fnext[(e * ROWS + rowA + u) * WAVE + lane], acc[e][u]);
+                        atomicMin(&Fnext[(e * ROWS + rowB + u) * WAVE + lane], acc[e][8 + u]);
+                    }
+                __syncthreads();
+                int32_t *tmp = Fprev; Fprev = Fnext; Fnext = tmp;
+#pragma unroll
+                for (int e = 0; e < NC; ++e) f1[e] = Fprev[e * ROWS * WAVE + lane];   // row 0
+            }
+#pragma unroll
+            for (int e = 0; e < NC; ++e)
+                if (f1[e] < best[e]) { best[e] = f1[e]; sbest[e] = s; }   // lowest s on ties
+            if (DUMP) {
+                int32_t *Fs = F_out + (size_t)s * LS;
+                if (WI == 1) {
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const int k = (u < 8 ? rowA : rowB - 8) + u;
+                        const bool in = lane < D;
+                        if (k < K) Fs[(k + 1) * (D + 1) + (in ? lane + 1 : 0)] = in ? acc[0][u] : DEV_INF;
+                    }
+                } else {
+                    // lanes beyond the mesh rewrite the row's d = 0 cell with infinity
+                    // (a select, not a branch on the lane id: see the ticket comment)
+                    for (int x = tid; x < K * WAVE; x += NT) {
+                        const int k = x >> 6, l = x & (WAVE - 1);
+                        const bool in = l < D;
+                        Fs[(k + 1) * (D + 1) + (in ? l + 1 : 0)] = in ? Fprev[x] : DEV_INF;
+                    }
+                }
+            }
+        }
+        // lane D-1 (of window (D-1)/64) holds F(s, first layer, all devices); wave 0 owns the
+        // results; a repeated last candidate goes to the spare slot
+#pragma unroll
+        for (int e = 0; e < NCAND; ++e) {
+            const int32_t bv = (WIDE && D > WAVE) ? best[NC - 1] : best[e];
+            const int32_t sv = (WIDE && D > WAVE) ? sbest[NC - 1] : sbest[e];
+            const int32_t bestD = __builtin_amdgcn_readlane(bv, (D - 1) & (WAVE - 1));
+            const int32_t sD = __builtin_amdgcn_readlane(sv, (D - 1) & (WAVE - 1));
+            const bool owner = (wid == 0) && (j0 + e < n);
+            const int slot = owner ? jj[e] : dummy_idx;
+            Fmin[slot] = bestD;                        // all lanes, same value
+            Sbest[slot] = bestD >= DEV_INF ? 0 : sD;
+            if (prune) {                               // uniform; the minimum is idempotent
+                const long long T = (owner && bestD < DEV_INF)
+                                        ? (long long)bestD + (long long)(p.B - 1) * (long long)c[e]
+                                        : (long long)INF_I64;
+                atomicMin((long long *)&chunk_min[jj[e] / PRUNE_CHUNK], T);
+            }
+        }
+        if (COUNT) n_blocks_total += n_blocks;
+        __syncthreads();                               // LDS is reused by the next group
+    }
+    if (COUNT) atomicAdd(wave_relax, lane == 0 ? n_blocks_total * 8ull : 0ull);
+}
+
+// shape-axis wave groups of the single-candidate (plan) run: as many as 1024 threads allow
+constexpr int plan_wi(int NWK) { return NWK > 4 ? 2 : 4; }
+
+template <int NWK, int WI, int NC>
+static size_t fast_lds_bytes()
+{
+    return (size_t)NC * (NWK * 16 + 6) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
+}
+
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
+static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
+{
+    const size_t lds = fast_lds_bytes<NWK, WI, NC>();
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(
+            (const void *)recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE>,
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE>), dim3(grid),
+                       dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
+                       a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
+                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p, a.group_min);
+    return hipGetLastError();
+}
+
+template <int NWK>
+static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc, int grid)
+{
+    switch (mode) {
+    case FAST_MODE_PLAN: return launch_one<NWK, plan_wi(NWK), 1, true, false>(st, a, grid);
+    case FAST_MODE_COUNT:
+        if (a.p.D > WAVE) {
+            if constexpr (NWK <= 4)   // two windows: up to 64 layers only
+                return launch_one<NWK, 1, 2, false, true, true>(st, a, grid);
+            else
+                return hipErrorInvalidValue;
+        }
+        return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
+                       : launch_one<NWK, 1, 1, false, true>(st, a, grid);
+    default:
+        if (a.p.D > WAVE) {
+            if constexpr (NWK <= 4)   // two windows: up to 64 layers only
+                return launch_one<NWK, 1, 2, false, false, true>(st, a, grid);
+            else
+                return hipErrorInvalidValue;
+        }
+        return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
+                       : launch_one<NWK, 1, 1, false, false>(st, a, grid);
+    }
+}
+
+template <int NWK, int NC>
+static int blocks_per_cu()
+{
+    int nb = 0;
+    const size_t lds = fast_lds_bytes<NWK, 1, NC>();
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)recurrence_fast_kernel<NWK, 1, NC, false, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+        &nb, recurrence_fast_kernel<NWK, 1, NC, false, false>, WAVE * NWK, lds);
+    return e == hipSuccess ? nb : 0;
+}
+
+}  // namespace alpa

@@ -167,6 +167,9 @@ struct FastArgs {
 enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);
 int fast_kernel_blocks_per_cu(int K, int nc);
+// the instances for 65-128 layers (kernels_fast_deep.hip)
+hipError_t launch_recurrence_fast_deep(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);
+int fast_kernel_blocks_per_cu_deep(int K, int nc);
 
 hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand,
                            const int32_t *Fmin, const int32_t *Sbest, SolveState *state, int prune,

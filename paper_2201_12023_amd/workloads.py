@@ -205,6 +205,26 @@ def make_workload(idx: int) -> Workload:
     raise ValueError("workload index must be 1..5")
 
 
+def deep_model_problem(seed: int, K: int, N: int, M: int, B: int = 64) -> Workload:
+    """A formula table of the MoE-like kind for any layer count (deeper models than the five
+    numbered workloads: up to 128 layers), with the memory cap scaled to the depth."""
+    rng = SplitMix64(seed)
+    cost = np.zeros(K, np.int64); mem = np.zeros(K, np.int64)
+    expert = np.zeros(K, np.int64)
+    for l in range(K):
+        if l % 2 == 0:
+            cost[l] = rng.uint(500, 700); mem[l] = rng.uint(2, 3)
+        else:
+            cost[l] = rng.uint(2000, 2800); mem[l] = rng.uint(16, 24)
+            expert[l] = 1
+    shapes = submesh_shapes(N, M)
+    terms = {}
+    cap = max(24, (80 * K * 64) // (64 * N * M))
+    table = _formula_table(K, shapes, cost, mem, 3, cap, expert=expert, terms=terms)
+    return Workload("deep", K, N, M, B, shapes, table, "quantiles", 4096, False, seed,
+                    cost, mem, np.full(K, 3, np.int64), terms)
+
+
 def _round_half_away(x: float) -> int:
     import math
     return int(math.floor(abs(x) + 0.5)) * (1 if x >= 0 else -1)

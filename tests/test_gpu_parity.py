@@ -421,3 +421,56 @@ def test_meshes_of_65_to_128_devices(case, kernel):
                 _same_plan(plans[1], p_ref)
         finally:
             B.alpa_dp_destroy(h)
+
+
+DEEP_CASES = [  # seed, K, N, M: 65..128 layers on at most 64 devices (5-8 waves per workgroup)
+    (70, 65, 4, 8), (71, 80, 8, 8), (72, 96, 2, 8), (73, 128, 8, 8), (74, 100, 1, 8),
+    (75, 113, 4, 16), (76, 128, 3, 4), (77, 81, 1, 1),
+]
+
+
+@pytest.mark.parametrize("kernel", list(KERNELS))
+@pytest.mark.parametrize("case", DEEP_CASES, ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_models_of_65_to_128_layers(case, kernel):
+    seed, K, N, M = case
+    rng = np.random.default_rng(seed)
+    w = W.random_problem(seed, K, N, M, inf_frac=float(rng.choice([0.0, 0.2, 0.5])),
+                         value_hi=int(rng.choice([6, 60, 6000])))
+    cand_ref = oracle.all_candidates(w.table, w.shapes)
+    if len(cand_ref) > 60:
+        cand_ref = oracle.quantiles(cand_ref, 60)
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            flags = KERNELS[kernel] | (B.ALPA_DP_PRUNE if prune else 0)
+            T, plan = B.alpa_dp_solve(h, cand_ref, flags=flags)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+            if not prune:
+                plans = B.alpa_dp_solve_sweep(h, cand_ref, [1, w.B, 50], flags=flags)
+                _same_plan(plans[1], p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("nc", ["1", "2"])
+@pytest.mark.parametrize("case", [(1, 128, 8, 8), (2, 96, 4, 8), (3, 72, 2, 8)],
+                         ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_deep_formula_tables(case, nc, monkeypatch):
+    """Structured tables (monotone in the stage span, memory-bound infeasibility) are where
+    the early stop of the column loops and the packed two-candidate passes take effect."""
+    monkeypatch.setenv("ALPA_DP_NC", nc)
+    seed, K, N, M = case
+    w = W.deep_model_problem(seed, K, N, M)
+    cand_ref = oracle.quantiles(oracle.all_candidates(w.table, w.shapes), 121)
+    for prune in (False, True):
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
+        assert (T_ref < oracle.INF64).any()
+        h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+        try:
+            T, plan = B.alpa_dp_solve(h, cand_ref, flags=B.ALPA_DP_PRUNE if prune else 0)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
+        finally:
+            B.alpa_dp_destroy(h)
