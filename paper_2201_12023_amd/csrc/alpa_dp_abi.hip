@@ -239,15 +239,14 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
     h->generic_grid_max = gg;
     HIPCHK(hipMalloc(&h->d_scratch, (size_t)gg * 2 * LS * 4));
     // register/LDS kernel
-    // up to 128 layers on up to 64 devices; above 64 devices (one candidate per workgroup, the
-    // two-window form of the kernel) up to 64 layers
-    h->fast_ok = (K <= 128 && D <= 64) || (K <= 64 && D <= 128);
+    // above 64 devices: one candidate per workgroup, the two-window form of the kernel
+    h->fast_ok = K <= 128 && D <= 128;
     if (h->fast_ok) {
         h->KP = 16 * ((K + 15) / 16);
         HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
-        HIPCHK(hipMalloc(&h->d_gmin, fast_group_min_ints(K, S) * 4));
+        HIPCHK(hipMalloc(&h->d_gmin, fast_group_min_ints(K, D, S) * 4));
         HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
-        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs, h->d_gmin));
+        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, D, S, h->KP, h->d_recs, h->d_gmin));
         for (int nc = 1; nc <= 2; ++nc) {
             int per_cu = fast_kernel_blocks_per_cu(K, nc);
             if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
@@ -383,11 +382,11 @@ extern "C" int alpa_dp_restrict_equal_layers(alpa_dp_t *h)
     if (prev != h->device) HIPCHK(hipSetDevice(h->device));
     struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
         restore{prev, h->device};
-    const int K = h->p.K, S = h->p.S;
+    const int K = h->p.K, D = h->p.D, S = h->p.S;
     HIPCHK(launch_equal_layer_mask(h->stream, h->d_table, K, S));
     if (h->fast_ok) {
         HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
-        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, S, h->KP, h->d_recs, h->d_gmin));
+        HIPCHK(launch_repack_fast(h->stream, h->d_table, K, D, S, h->KP, h->d_recs, h->d_gmin));
     }
     // the candidate list changes with the table; the running best belonged to the old one
     int rc = queue_table_candidates(h);

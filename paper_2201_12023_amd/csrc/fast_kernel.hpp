@@ -1,5 +1,5 @@
-// Register/LDS recurrence kernel (Eq. 3) for K <= 128 layers on N*M <= 64 devices, and for
-// K <= 64 layers on up to 128 devices in a two-window form (see WIDE below).
+// Register/LDS recurrence kernel (Eq. 3) for K <= 128 layers on N*M <= 64 devices, and on up
+// to 128 devices in a two-window form (see WIDE below).
 //
 // Mapping.  One workgroup evaluates one t_max candidate at a time (persistent workgroups
 // draw candidates from a ticket counter).  Lane l of every wave owns device count
@@ -184,7 +184,10 @@ void recurrence_fast_kernel(
     extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
     __shared__ int32_t sh_tk[NT];
     __shared__ int32_t sh_skip[NWK * WI];
-    __shared__ int32_t sh_ends[NWK * WI * (END_SHAPES / 4) * WAVE];   // early-stop table
+    // stage counts the early-stop table spans: 64, or 128 for more than 64 layers on more
+    // than 64 devices (stage counts never exceed either)
+    constexpr int SW = (WIDE && NWK > 4) ? 2 * WAVE : WAVE;
+    __shared__ int32_t sh_ends[NWK * WI * (END_SHAPES / 4) * SW];     // early-stop table
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -265,24 +268,27 @@ void recurrence_fast_kernel(
         {
             const int32_t cmax = c[NC - 1];
             constexpr int NHB = KP / 8;
+#pragma nounroll
+            for (int ls = lane; ls < SW; ls += WAVE) { // s - 1 served by this lane
             int32_t word = 0;
 #pragma nounroll
             for (int q = 0; q < END_SHAPES; ++q) {     // rows of shapes >= S are never read
                 if (q < S) {
-                    const int32_t *gA = group_min + ((q * NHB + hbA) * END_GROUPS) * WAVE + lane;
-                    const int32_t *gB = group_min + ((q * NHB + hbB) * END_GROUPS) * WAVE + lane;
+                    const int32_t *gA = group_min + ((q * NHB + hbA) * END_GROUPS) * SW + ls;
+                    const int32_t *gB = group_min + ((q * NHB + hbB) * END_GROUPS) * SW + ls;
                     int nA = 0, nB = 0;
 #pragma unroll
                     for (int j = 0; j < END_GROUPS; ++j) {
-                        nA += gA[j * WAVE] <= cmax ? 1 : 0;
-                        nB += gB[j * WAVE] <= cmax ? 1 : 0;
+                        nA += gA[j * SW] <= cmax ? 1 : 0;
+                        nB += gB[j * SW] <= cmax ? 1 : 0;
                     }
                     word |= (nA | (nB << 4)) << (8 * (q & 3));
                 }
                 if ((q & 3) == 3) {                    // four shapes per word
-                    sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + lane] = word;
+                    sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * SW + ls] = word;
                     word = 0;
                 }
+            }
             }
         }
         int32_t best[NC], sbest[NC];
@@ -325,7 +331,7 @@ void recurrence_fast_kernel(
                 int endA = K, endB = K;
                 if (q < END_SHAPES) {
                     const int bits = __builtin_amdgcn_readfirstlane(
-                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * WAVE + s - 1]) >> (8 * (q & 3));
+                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * SW + s - 1]) >> (8 * (q & 3));
                     endA = needA ? GW * (bits & 15) : 0;
                     endB = needB ? GW * ((bits >> 4) & 15) : 0;
                 }
@@ -613,21 +619,11 @@ static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc
     switch (mode) {
     case FAST_MODE_PLAN: return launch_one<NWK, plan_wi(NWK), 1, true, false>(st, a, grid);
     case FAST_MODE_COUNT:
-        if (a.p.D > WAVE) {
-            if constexpr (NWK <= 4)   // two windows: up to 64 layers only
-                return launch_one<NWK, 1, 2, false, true, true>(st, a, grid);
-            else
-                return hipErrorInvalidValue;
-        }
+        if (a.p.D > WAVE) return launch_one<NWK, 1, 2, false, true, true>(st, a, grid);
         return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
                        : launch_one<NWK, 1, 1, false, true>(st, a, grid);
     default:
-        if (a.p.D > WAVE) {
-            if constexpr (NWK <= 4)   // two windows: up to 64 layers only
-                return launch_one<NWK, 1, 2, false, false, true>(st, a, grid);
-            else
-                return hipErrorInvalidValue;
-        }
+        if (a.p.D > WAVE) return launch_one<NWK, 1, 2, false, false, true>(st, a, grid);
         return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
                        : launch_one<NWK, 1, 1, false, false>(st, a, grid);
     }

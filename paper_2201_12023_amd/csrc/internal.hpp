@@ -139,10 +139,11 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
 hipError_t launch_valu_peak(hipStream_t st, int grid, int iters, int32_t *sink);
 hipError_t launch_equal_layer_mask(hipStream_t st, int32_t *table, int K, int S);
 
-hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
+hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int D, int S, int KP,
                               int32_t *recs, int32_t *group_min);
 size_t fast_table_ints(int K, int S);    // size of the column-record array, padding included
-size_t fast_group_min_ints(int K, int S);   // size of the early-stop table
+int fast_group_min_stages(int K, int D);        // stage counts the early-stop table spans
+size_t fast_group_min_ints(int K, int D, int S);   // size of the early-stop table
 
 hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int32_t *table,
                                      const int32_t *sizes, const int32_t *cand,

@@ -37,45 +37,49 @@ __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int
 // Second pass of the repack.  For every (q, half-block, group j of 8 columns (see end_group_cols), s) the minimum of
 // t_intra over the half-block's first layers and all last layers >= 8j: a candidate below it
 // finds nothing in column 8j or any later one, so the column loops of that (s, q, half-block)
-// can stop there.  Layout g[q][hb][j][s - 1] with the s axis padded to 64: the kernel reads it
-// with lane = s - 1 (stage counts never exceed the device count, 64 whenever this table is used
-// for more than 64 layers).  Beyond 64 layers a group is KP / 8 columns wide.
-__global__ void repack_group_min_kernel(int K, int S, int KP, const int32_t *__restrict__ recs,
+// can stop there.  Layout g[q][hb][j][s - 1] with the s axis padded to SW = 64 (128 for more
+// than 64 layers on more than 64 devices; stage counts exceed neither): the kernel reads it
+// with lane = (s - 1) % 64.  Beyond 64 layers a group is KP / 8 columns wide.
+__global__ void repack_group_min_kernel(int K, int S, int KP, int SW, const int32_t *__restrict__ recs,
                                         int32_t *__restrict__ g)
 {
     const int NHB = KP / 8;
-    const int total = S * NHB * WAVE;                  // one thread per (q, hb, s - 1)
+    const int total = S * NHB * SW;                    // one thread per (q, hb, s - 1)
     for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
-        const int s1 = e % WAVE;
-        const int hb = (e / WAVE) % NHB;
-        const int q = e / (WAVE * NHB);
+        const int s1 = e % SW;
+        const int hb = (e / SW) % NHB;
+        const int q = e / (SW * NHB);
         const int GW = end_group_cols(KP);
         int32_t run = 0x3f3f3f3f;                      // above DEV_INF: never alive
         for (int j = END_GROUPS - 1; j >= 0; --j) {
             if (s1 < K)
                 for (int i = min(K, GW * j + GW) - 1; i >= GW * j; --i)
                     run = min(run, recs[((((long long)s1 * S + q) * K + i) * NHB + hb) * HB_INTS]);
-            g[((q * NHB + hb) * END_GROUPS + j) * WAVE + s1] = run;
+            g[((q * NHB + hb) * END_GROUPS + j) * SW + s1] = run;
         }
     }
 }
 
-hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int S, int KP,
+hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int D, int S, int KP,
                               int32_t *recs, int32_t *group_min)
 {
     long long total = (long long)K * K * S * (KP / 8);
     int grid = (int)((total + 255) / 256);
     if (grid > 8192) grid = 8192;
     hipLaunchKernelGGL(repack_fast_kernel, dim3(grid), dim3(256), 0, st, table, K, S, KP, recs);
-    const int n_chains = S * (KP / 8) * WAVE;
+    const int SW = fast_group_min_stages(K, D);
+    const int n_chains = S * (KP / 8) * SW;
     hipLaunchKernelGGL(repack_group_min_kernel, dim3((n_chains + 63) / 64), dim3(64), 0, st, K, S,
-                       KP, recs, group_min);
+                       KP, SW, recs, group_min);
     return hipGetLastError();
 }
 
-size_t fast_group_min_ints(int K, int S)
+// stage counts the early-stop table spans (the kernel's SW)
+int fast_group_min_stages(int K, int D) { return (K > 64 && D > WAVE) ? 2 * WAVE : WAVE; }
+
+size_t fast_group_min_ints(int K, int D, int S)
 {
-    return (size_t)S * ((K + 15) / 16 * 2) * END_GROUPS * WAVE;
+    return (size_t)S * ((K + 15) / 16 * 2) * END_GROUPS * fast_group_min_stages(K, D);
 }
 
 size_t fast_table_ints(int K, int S)

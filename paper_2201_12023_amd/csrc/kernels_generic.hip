@@ -2,9 +2,8 @@
 // selection, and plan recovery.  The recurrence here is the straightforward one: one
 // workgroup per t_max candidate, threads over the cells (k, d) of a layer s, every cell
 // scanning its (last layer, shape) terms in tie-break order; F layers live in global
-// memory.  Problems of up to 128 layers on up to 64 devices, and of up to 64 layers on up to
-// 128 devices, normally run through the register/LDS kernel (fast_kernel.hpp); this one
-// serves the remaining sizes and recovers the plan of the winning candidate where that
+// memory.  Problems of up to 128 layers on up to 128 devices normally run through the
+// register/LDS kernel (fast_kernel.hpp); this one serves the remaining sizes and recovers the plan of the winning candidate where that
 // kernel does not (it keeps every layer s when asked to).
 #include "internal.hpp"
 

@@ -251,6 +251,25 @@ def random_problem(seed: int, K: int, N: int, M: int, *, S_extra_dup: bool = Fal
                     np.ascontiguousarray(table.astype(np.int32)), "all", 0, False, seed)
 
 
+def many_stage_problem(seed: int, K: int, N: int, M: int, B: int = 512) -> Workload:
+    """A table on which more devices buy no speed (latency = 1000 per layer + 40 per extra
+    device + noise below 50) and many microbatches: the optimum cuts the model into nearly as
+    many one-device stages as layers or devices allow, so stage counts far above those of
+    the model-like workloads are exercised."""
+    rng = np.random.default_rng(seed)
+    shapes = submesh_shapes(N, M)
+    S = shapes.shape[0]
+    a = shapes[:, 0].astype(np.int64) * shapes[:, 1]
+    kk = np.arange(K)[:, None]
+    ii = np.arange(K)[None, :]
+    lat = 1000 * (ii - kk + 1)[:, :, None] + 40 * (a - 1)[None, None, :]
+    lat = lat + rng.integers(0, 50, size=(K, K, S))
+    table = np.broadcast_to(lat[None], (K, K, K, S)).copy()
+    table[:, ii < kk, :] = int(INF_I32)
+    return Workload(f"stages{seed}", K, N, M, B, shapes.astype(np.int32),
+                    np.ascontiguousarray(table.astype(np.int32)), "quantiles", 16, False, seed)
+
+
 # ---------------------------------------------------------------------------------------------
 # Profiled options: the inputs of the table-construction step (Sec. 5.2, Eq. 5; Alg. 1's
 # "run the intra-op pass" loop nest).  Only inputs are made here; the step itself (pick the

@@ -50,9 +50,10 @@ def test_mask_keeps_exactly_the_equal_length_entries():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("idx", [1, 2, 5])
+@pytest.mark.parametrize("idx", [1, 2, 5, "deep"])
 def test_restricted_handle_against_the_oracle(idx):
-    w = W.make_workload(idx)
+    # "deep": 96 layers on a 2x8 mesh, the 6-wave form of the register/LDS kernel
+    w = W.deep_model_problem(5, 96, 2, 8) if idx == "deep" else W.make_workload(idx)
     masked = oracle.equal_layer_table(w.table)
     cand = oracle.all_candidates(masked, w.shapes)
     cand_q = oracle.quantiles(cand, 40)

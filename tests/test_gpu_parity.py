@@ -423,9 +423,11 @@ def test_meshes_of_65_to_128_devices(case, kernel):
             B.alpa_dp_destroy(h)
 
 
-DEEP_CASES = [  # seed, K, N, M: 65..128 layers on at most 64 devices (5-8 waves per workgroup)
+DEEP_CASES = [  # seed, K, N, M: 65..128 layers (5-8 waves per workgroup), the last four on
+    # 65..128 devices (two windows, stage counts up to 128)
     (70, 65, 4, 8), (71, 80, 8, 8), (72, 96, 2, 8), (73, 128, 8, 8), (74, 100, 1, 8),
     (75, 113, 4, 16), (76, 128, 3, 4), (77, 81, 1, 1),
+    (78, 70, 9, 8), (79, 100, 16, 8), (80, 128, 2, 64), (81, 128, 16, 8),
 ]
 
 
@@ -437,8 +439,9 @@ def test_models_of_65_to_128_layers(case, kernel):
     w = W.random_problem(seed, K, N, M, inf_frac=float(rng.choice([0.0, 0.2, 0.5])),
                          value_hi=int(rng.choice([6, 60, 6000])))
     cand_ref = oracle.all_candidates(w.table, w.shapes)
-    if len(cand_ref) > 60:
-        cand_ref = oracle.quantiles(cand_ref, 60)
+    n_q = 60 if K * N * M <= 8192 else 20          # the oracle's time on the largest sizes
+    if len(cand_ref) > n_q:
+        cand_ref = oracle.quantiles(cand_ref, n_q)
     for prune in (False, True):
         T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
         h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
@@ -452,6 +455,27 @@ def test_models_of_65_to_128_layers(case, kernel):
                 _same_plan(plans[1], p_ref)
         finally:
             B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("kernel", list(KERNELS))
+@pytest.mark.parametrize("case", [(1, 128, 16, 8, 65), (2, 100, 16, 8, 65), (3, 90, 9, 8, 40),
+                                  (4, 64, 16, 8, 50), (5, 128, 8, 8, 50)],
+                         ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_plans_of_many_stages(case, kernel):
+    """Optima with up to 100 stages (more than 64 on the 16x8 mesh): the upper stage counts of
+    the recurrence, of the early-stop table and of plan recovery."""
+    seed, K, N, M, at_least = case
+    w = W.many_stage_problem(seed, K, N, M)
+    cand_ref = oracle.quantiles(oracle.all_candidates(w.table, w.shapes), 16)
+    T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, False, 8)
+    assert p_ref.num_stages >= at_least
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        T, plan = B.alpa_dp_solve(h, cand_ref, flags=KERNELS[kernel])
+        assert (T == T_ref).all()
+        _same_plan(plan, p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
 
 
 @pytest.mark.parametrize("nc", ["1", "2"])

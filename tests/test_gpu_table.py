@@ -77,6 +77,28 @@ def test_workload_profiles_table_and_dp_on_top(idx):
         B.alpa_dp_destroy(h)
 
 
+def test_deep_model_profiles_table_and_dp_on_top():
+    """100 layers on a 4x8 mesh: the table built on the device feeds the 7-wave form of the
+    register/LDS kernel."""
+    K, N, M, Bm = 100, 4, 8, 16
+    shapes = W.submesh_shapes(N, M)
+    p = W.random_profiles(21, K, len(shapes), 3, absent_frac=0.2)
+    ref = oracle.build_table(p.t_l, p.mem_stage, p.mem_act, p.mem_device)
+    h = B.alpa_dp_create_from_profiles(p.t_l, p.mem_stage, p.mem_act, p.mem_device, K, N, M, Bm,
+                                       shapes)
+    try:
+        assert (B.alpa_dp_get_table(h, K, len(shapes)) == ref).all()
+        cand = oracle.quantiles(oracle.all_candidates(ref, shapes), 24)
+        T_ref, p_ref = oracle.solve_parallel(ref, N, M, Bm, shapes, cand, False, 8)
+        T, plan = B.alpa_dp_solve(h, None, 24, 0)
+        assert (B.alpa_dp_candidates(h) == cand).all()
+        assert (T == T_ref).all()
+        assert plan["T_star"] == p_ref.T_star and plan["t_max"] == p_ref.t_max
+        assert plan["first_layer"] == p_ref.first_layer and plan["shape_idx"] == p_ref.shape_idx
+    finally:
+        B.alpa_dp_destroy(h)
+
+
 @pytest.mark.parametrize("idx", [2, 4])
 def test_single_option_profiles_give_the_workload_table(idx):
     w = W.make_workload(idx)
