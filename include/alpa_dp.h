@@ -201,8 +201,8 @@ int alpa_dp_solve_dev(alpa_dp_t *h, const int32_t *d_tmax, int n_tmax, unsigned 
  * The handle's own B and the running best of alpa_dp_best() are not touched.  Blocking.
  * On the first call (and when n_B grows) device memory for n_B sets of layers is
  * allocated: n_B * (min(K, N*M) + 1) * (K + 2) * (N*M + 1) * 4 bytes when K <= 128 and
- * N*M <= 64 (one set, reused, otherwise).  Errors: EINVAL (null pointers, n_B or a B value out of range, and the
- * candidate-list errors of alpa_dp_solve), ENOMEM, EHIP.
+ * N*M <= 64 (one set, reused, otherwise).  Errors: EINVAL (null pointers, n_B or a B value
+ * out of range, and the candidate-list errors of alpa_dp_solve), ENOMEM, EHIP.
  */
 #define ALPA_DP_MAX_SWEEP 256
 int alpa_dp_solve_sweep(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned flags,
