@@ -148,6 +148,14 @@ static int bits_for(uint32_t v)
 // distinct finite table values -> d_distinct, count -> d_ncount[0]
 static int queue_table_candidates(alpa_dp *h)
 {
+    // small values: one bit per value instead of a sort (the second key buffer is the work area)
+    if (h->max_finite >= 0 && h->max_finite < DISTINCT_BITMAP_MAX && !getenv("ALPA_DP_SORT") &&
+        distinct_bitmap_words(h->max_finite) <= (size_t)h->pb.cap) {
+        HIPCHK(launch_distinct_by_bitmap(h->stream, h->d_table, h->p.K, h->p.S, h->max_finite,
+                                         (uint32_t *)h->pb.keys[1], h->d_distinct,
+                                         h->d_ncount + 0));
+        return ALPA_DP_OK;
+    }
     const int32_t inf_key = h->max_finite + 1;
     HIPCHK(launch_gather_table_values(h->stream, h->d_table, h->p.K, h->p.S, inf_key,
                                       h->pb.keys[0]));

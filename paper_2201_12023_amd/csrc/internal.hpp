@@ -123,6 +123,12 @@ hipError_t launch_gather_table_values(hipStream_t st, const int32_t *table, int 
                                       int32_t inf_key, int32_t *out_keys);
 hipError_t launch_sort_dedup(hipStream_t st, PrepBuffers &pb, int n, int key_bits,
                              int32_t drop_key, int32_t *out_unique, uint32_t *out_n_unique);
+// values below this many bits' worth go through the presence bitmap instead of the sort
+constexpr int32_t DISTINCT_BITMAP_MAX = 1 << 19;
+hipError_t launch_distinct_by_bitmap(hipStream_t st, const int32_t *table, int K, int S,
+                                     int32_t max_value, uint32_t *work, int32_t *out_unique,
+                                     uint32_t *out_n_unique);
+size_t distinct_bitmap_words(int32_t max_value);
 hipError_t launch_pick_candidates(hipStream_t st, const int32_t *distinct,
                                   const uint32_t *n_distinct, int n_quantiles, int32_t *cand,
                                   SolveState *state, int cap);

@@ -223,6 +223,90 @@ __global__ __launch_bounds__(1024) void dedup_write_kernel(const int32_t *__rest
         if (f[u]) unique[pos++] = keys[base + u];
 }
 
+// ---------------------------------------------------------------- distinct values by bitmap
+//
+// SortedAndFilter of Alg. 1 for tables whose finite values are small integers (below
+// DISTINCT_BITMAP_MAX, so that the bitmap fits a workgroup's 64 KiB of LDS): instead of sorting every entry, each finite entry sets one bit of a
+// presence bitmap and the set bits are listed in order; the result is the same ascending list
+// of distinct values.
+
+__global__ void bitmap_clear_kernel(uint32_t *__restrict__ bm, int words)
+{
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < words; x += gridDim.x * blockDim.x)
+        bm[x] = 0u;
+}
+
+// Every block marks its share of the table in a bitmap of its own in LDS (most entries repeat
+// values the block has already seen) and then merges the words it touched into the global one.
+__global__ __launch_bounds__(1024) void bitmap_mark_kernel(const int32_t *__restrict__ table, int K,
+                                                           int S, int words,
+                                                           uint32_t *__restrict__ bm)
+{
+    extern __shared__ uint32_t lbm[];             // [words]
+    for (int x = threadIdx.x; x < words; x += blockDim.x) lbm[x] = 0u;
+    __syncthreads();
+    const long long total = (long long)K * K * K * S;
+    for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        const long long r = e / S;
+        const int i = (int)(r % K), k = (int)((r / K) % K);
+        if (i < k) continue;
+        const int32_t t = table[e];
+        if (t == INF_I32) continue;
+        const uint32_t bit = 1u << (t & 31);
+        if (!(lbm[t >> 5] & bit)) atomicOr(&lbm[t >> 5], bit);   // a stale 0 only costs the atomic
+    }
+    __syncthreads();
+    for (int x = threadIdx.x; x < words; x += blockDim.x) {
+        const uint32_t v = lbm[x];
+        if (v && (v & ~__atomic_load_n(&bm[x], __ATOMIC_RELAXED))) atomicOr(&bm[x], v);
+    }
+}
+
+__global__ __launch_bounds__(1024) void bitmap_count_kernel(const uint32_t *__restrict__ bm,
+                                                            int words,
+                                                            uint32_t *__restrict__ block_cnt)
+{
+    __shared__ uint32_t wsum[16];
+    const int t = threadIdx.x;
+    const int x = blockIdx.x * 1024 + t;
+    uint32_t c = x < words ? __popc(bm[x]) : 0u;
+    for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
+    if ((t & 63) == 0) wsum[t >> 6] = c;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t s = 0;
+        for (int w = 0; w < 16; ++w) s += wsum[w];
+        block_cnt[blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(1024) void bitmap_write_kernel(const uint32_t *__restrict__ bm,
+                                                            int words,
+                                                            const uint32_t *__restrict__ block_off,
+                                                            int32_t *__restrict__ unique)
+{
+    __shared__ uint32_t part[1024];
+    const int t = threadIdx.x;
+    const int x = blockIdx.x * 1024 + t;
+    uint32_t w = x < words ? bm[x] : 0u;
+    const uint32_t c = __popc(w);
+    part[t] = c;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        uint32_t o = (t >= off) ? part[t - off] : 0u;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    uint32_t pos = block_off[blockIdx.x] + part[t] - c;
+    while (w) {                                   // set bits, lowest first
+        const int b = __ffs(w) - 1;
+        unique[pos++] = (x << 5) + b;
+        w &= w - 1;
+    }
+}
+
 // ---------------------------------------------------------------- candidate lists
 
 __global__ void pick_candidates_kernel(const int32_t *__restrict__ distinct,
@@ -303,6 +387,34 @@ hipError_t launch_sort_dedup(hipStream_t st, PrepBuffers &pb, int n, int key_bit
     hipLaunchKernelGGL(dedup_write_kernel, dim3(nb), dim3(1024), 0, st, pb.keys[cur], n, drop_key,
                        pb.block_cnt, out_unique);
     return hipGetLastError();
+}
+
+// Ascending distinct finite values of the table's entries with last >= first layer, all known
+// to be <= max_value < DISTINCT_BITMAP_MAX, to out_unique and their count to *out_n_unique.
+// `work` holds the bitmap and the block counts: distinct_bitmap_words(max_value) uint32.
+hipError_t launch_distinct_by_bitmap(hipStream_t st, const int32_t *table, int K, int S,
+                                     int32_t max_value, uint32_t *work, int32_t *out_unique,
+                                     uint32_t *out_n_unique)
+{
+    const int words = max_value / 32 + 1;
+    const int nb = (words + 1023) / 1024;
+    uint32_t *bm = work, *block_cnt = work + words;
+    hipLaunchKernelGGL(bitmap_clear_kernel, dim3(std::min(nb, 256)), dim3(1024), 0, st, bm, words);
+    const long long total = (long long)K * K * K * S;
+    const int grid = (int)std::min<long long>((total + 8191) / 8192, 256);
+    hipLaunchKernelGGL(bitmap_mark_kernel, dim3(grid), dim3(1024), (size_t)words * 4, st, table, K,
+                       S, words, bm);
+    hipLaunchKernelGGL(bitmap_count_kernel, dim3(nb), dim3(1024), 0, st, bm, words, block_cnt);
+    hipLaunchKernelGGL(scan_u32_kernel, dim3(1), dim3(1024), 0, st, block_cnt, nb, out_n_unique);
+    hipLaunchKernelGGL(bitmap_write_kernel, dim3(nb), dim3(1024), 0, st, bm, words, block_cnt,
+                       out_unique);
+    return hipGetLastError();
+}
+
+size_t distinct_bitmap_words(int32_t max_value)
+{
+    const size_t words = (size_t)max_value / 32 + 1;
+    return words + (words + 1023) / 1024 + 1;
 }
 
 hipError_t launch_pick_candidates(hipStream_t st, const int32_t *distinct,

@@ -498,3 +498,38 @@ def test_deep_formula_tables(case, nc, monkeypatch):
             _same_plan(plan, p_ref)
         finally:
             B.alpa_dp_destroy(h)
+
+
+@pytest.mark.parametrize("force_sort", [False, True])
+@pytest.mark.parametrize("case", [  # seed, K, N, M, largest value
+    (90, 6, 2, 2, 50_000_000), (91, 9, 1, 4, (1 << 19) - 1), (92, 9, 1, 4, 1 << 19),
+    (93, 40, 4, 4, 3000), (94, 1, 1, 1, 7), (95, 12, 2, 8, 1), (96, 33, 8, 8, 400_000),
+], ids=lambda c: f"s{c[0]}-K{c[1]}-max{c[4]}")
+def test_candidate_list_by_bitmap_and_by_sort(case, force_sort, monkeypatch):
+    """The ascending distinct finite table values (the candidates when no list is given) come
+    from a presence bitmap when the largest value is below 2^19 and from a radix sort
+    otherwise; both against the oracle's list, with zeros, the extreme values present, and the
+    tuning variable that forces the sort."""
+    if force_sort:
+        monkeypatch.setenv("ALPA_DP_SORT", "1")
+    seed, K, N, M, hi = case
+    w = W.random_problem(seed, K, N, M, inf_frac=0.3, value_hi=hi)
+    tab = w.table.copy()
+    fin = np.argwhere(tab != oracle.INF32)
+    if len(fin) >= 2:                               # make sure both ends of the range occur
+        tab[tuple(fin[0])] = 0
+        tab[tuple(fin[-1])] = hi
+    ref = oracle.all_candidates(tab, w.shapes)
+    h = B.alpa_dp_create(tab, K, N, M, w.B, w.shapes)
+    try:
+        assert B.alpa_dp_count_candidates(h) == len(ref)
+        T, plan = B.alpa_dp_solve(h, None, 0, 0)
+        assert (B.alpa_dp_candidates(h) == ref).all()
+        T_ref, p_ref = oracle.solve_parallel(tab, N, M, w.B, w.shapes, ref[:200], False, 8)
+        assert (T[:200] == T_ref).all()
+        nq = 17
+        if len(ref) > nq:
+            B.alpa_dp_solve(h, None, nq, 0)
+            assert (B.alpa_dp_candidates(h) == oracle.quantiles(ref, nq)).all()
+    finally:
+        B.alpa_dp_destroy(h)
