@@ -533,3 +533,27 @@ def test_candidate_list_by_bitmap_and_by_sort(case, force_sort, monkeypatch):
             assert (B.alpa_dp_candidates(h) == oracle.quantiles(ref, nq)).all()
     finally:
         B.alpa_dp_destroy(h)
+
+
+def test_candidate_list_much_longer_than_the_table():
+    """A caller's list far longer than the table has entries (the per-candidate arrays grow),
+    with repeats and values between and beyond the table's; then the table's own list again."""
+    w = W.random_problem(77, 6, 2, 4, inf_frac=0.2, value_hi=900, B=5)
+    rng = np.random.default_rng(5)
+    tmax = rng.integers(0, 1200, size=60_000).astype(np.int32)
+    uniq = np.unique(tmax)
+    T_u, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, uniq, False, 8)
+    lookup = dict(zip(uniq.tolist(), T_u.tolist()))
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        for kernel in KERNELS.values():
+            T, plan = B.alpa_dp_solve(h, tmax, flags=kernel)
+            assert T.tolist() == [lookup[int(x)] for x in tmax]
+            _same_plan(plan, p_ref)
+        ref = oracle.all_candidates(w.table, w.shapes)
+        T2, _ = B.alpa_dp_solve(h, None, 0, 0)
+        assert (B.alpa_dp_candidates(h) == ref).all()
+        T2_ref, _ = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, ref, False, 8)
+        assert (T2 == T2_ref).all()
+    finally:
+        B.alpa_dp_destroy(h)
