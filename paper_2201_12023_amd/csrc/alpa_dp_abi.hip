@@ -538,10 +538,8 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
         } else {
             for (int b = 0; b < n_B; ++b) {        // one slab of layers, reused in stream order
                 SolveState *sb = h->d_sw_state + b;
-                HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, h->d_sw_c + b,
-                                                 &sb->plan_n, &sb->plan_ticket, nullptr, 0,
-                                                 h->d_tmpFS, h->d_tmpFS + 2, h->d_Fall,
-                                                 p.Smax + 1, 1, h->d_sw_s + b));
+                HIPCHK(launch_plan_layers(st, p, h->d_table, h->d_sizes, h->d_sw_c + b,
+                                          &sb->plan_n, h->d_sw_s + b, h->d_Fall));
                 HIPCHK(launch_plan_walk_many(st, p, h->d_table, h->d_sizes, sb, h->d_Fall, 0,
                                              h->d_sw_plans + b, 1));
             }
@@ -563,10 +561,8 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
                     h->d_gmin};
         HIPCHK(launch_recurrence_fast(st, fa, FAST_MODE_PLAN, 1, 1));
     } else {
-        HIPCHK(launch_recurrence_generic(st, p, h->d_table, h->d_sizes, &h->d_state->best_c,
-                                         &h->d_state->plan_n, &h->d_state->plan_ticket, nullptr, 0,
-                                         h->d_tmpFS, h->d_tmpFS + 2, h->d_Fall, p.Smax + 1, 1,
-                                         &h->d_state->best_s));
+        HIPCHK(launch_plan_layers(st, p, h->d_table, h->d_sizes, &h->d_state->best_c,
+                                  &h->d_state->plan_n, &h->d_state->best_s, h->d_Fall));
     }
     HIPCHK(launch_plan_walk(st, p, h->d_table, h->d_sizes, h->d_state, h->d_Fall, h->d_plan_tmp,
                             h->d_best_plan, d_out_plan));

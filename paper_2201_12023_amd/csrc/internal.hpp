@@ -155,7 +155,7 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      const int32_t *sizes, const int32_t *cand,
                                      const int32_t *n_cand_p, int32_t *ticket, int64_t *chunk_min,
                                      int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
-                                     int n_layers, int grid, const int32_t *s_top_p = nullptr);
+                                     int n_layers, int grid);
 struct FastArgs {
     Problem p;
     const int32_t *recs, *sizes, *cand, *n_cand_p;
@@ -178,6 +178,10 @@ int fast_kernel_blocks_per_cu(int K, int nc);
 hipError_t launch_recurrence_fast_deep(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);
 int fast_kernel_blocks_per_cu_deep(int K, int nc);
 
+// plan recovery of one candidate, a launch per layer (general sizes)
+hipError_t launch_plan_layers(hipStream_t st, const Problem &p, const int32_t *table,
+                              const int32_t *sizes, const int32_t *c_p, const int32_t *n_p,
+                              const int32_t *s_top_p, int32_t *F_all);
 hipError_t launch_epilogue(hipStream_t st, const Problem &p, const int32_t *cand,
                            const int32_t *Fmin, const int32_t *Sbest, SolveState *state, int prune,
                            int64_t *T);

@@ -3,8 +3,9 @@
 // workgroup per t_max candidate, threads over the cells (k, d) of a layer s, every cell
 // scanning its (last layer, shape) terms in tie-break order; F layers live in global
 // memory.  Problems of up to 128 layers on up to 128 devices normally run through the
-// register/LDS kernel (fast_kernel.hpp); this one serves the remaining sizes and recovers the plan of the winning candidate where that
-// kernel does not (it keeps every layer s when asked to).
+// register/LDS kernel (fast_kernel.hpp); this one serves the remaining sizes.  Where that
+// kernel does not recover the winner's layers itself (more than 64 devices), and for the
+// remaining sizes, plan_layer_kernel does, one launch per layer.
 #include "internal.hpp"
 
 namespace alpa {
@@ -12,13 +13,41 @@ namespace alpa {
 // F(s, k, d) of Eq. 3 for one candidate c, with F layers of (K+2) x (D+1) int32 each
 // (k = 0..K+1, layers 1-based, k = K+1 is the "past the end" row; d = 0..D).
 // layer(s) = slot + (s % n_layers) * layer_size.
-// band (plan recovery of a winner with s_top stages): only layers up to s_top are filled, and
-// of layer s only first layers k >= s_top - s + 1, the cells the walk back from (s_top, first
-// layer 1) can reach; the others keep +infinity.
+// F(s, k, d) of Eq. 3 for candidate c from layer s-1 (`prev`), k and d 1-based; k_min: first
+// layers below it are left at +infinity (the band of the plan-recovery run).
+__device__ __forceinline__ int32_t relax_cell(const Problem &p, const int32_t *__restrict__ tab_s,
+                                              const int32_t *__restrict__ sizes,
+                                              const int32_t *__restrict__ prev, int32_t c, int s,
+                                              int k, int d, int k_min)
+{
+    const int K = p.K, D = p.D, S = p.S;
+    int32_t v = DEV_INF;
+    // s stages need s layers and s devices: cells with k > K - s + 1 or d < s stay
+    // infinite, and an operand F(s-1, i+1, .) can only be finite for K - i >= s - 1
+    // (for s = 1 only the "past the end" row i + 1 = K + 1 is)
+    if (k >= k_min && k <= K - s + 1 && d >= s) {
+        const int i_first = (s == 1) ? K : k, i_last = K - s + 1;
+        for (int i = i_first; i <= i_last; ++i) {
+            const int32_t *tp = tab_s + ((size_t)(k - 1) * K + (i - 1)) * S;
+            const int32_t *prow = prev + (i + 1) * (D + 1);
+            for (int q = 0; q < S; ++q) {
+                const int a = sizes[q];
+                if (a > d) continue;
+                const int32_t t = tp[q];
+                if (t == INF_I32 || t > c) continue;
+                const int32_t f = prow[d - a];
+                if (f >= DEV_INF) continue;
+                const int32_t sum = t + f;
+                if (sum < v) v = sum;
+            }
+        }
+    }
+    return v;
+}
+
 __device__ void fill_layers(const Problem &p, const int32_t *__restrict__ table,
                             const int32_t *__restrict__ sizes, int32_t c, int32_t *slot,
-                            int n_layers, int s_top, bool band, int32_t *best_out,
-                            int32_t *sbest_out)
+                            int n_layers, int32_t *best_out, int32_t *sbest_out)
 {
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
@@ -27,34 +56,13 @@ __device__ void fill_layers(const Problem &p, const int32_t *__restrict__ table,
     for (int x = tid; x < LS; x += nt) slot[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
     __syncthreads();
     int32_t best = DEV_INF, sbest = 0;
-    for (int s = 1; s <= s_top; ++s) {
+    for (int s = 1; s <= p.Smax; ++s) {
         const int32_t *prev = slot + (size_t)((s - 1) % n_layers) * LS;
         int32_t *cur = slot + (size_t)(s % n_layers) * LS;
         const int32_t *tab_s = table + (size_t)(s - 1) * K * K * S;
         for (int x = tid; x < LS; x += nt) {
             const int k = x / (D + 1), d = x - k * (D + 1);
-            int32_t v = DEV_INF;
-            // s stages need s layers and s devices: cells with k > K - s + 1 or d < s stay
-            // infinite, and an operand F(s-1, i+1, .) can only be finite for K - i >= s - 1
-            // (for s = 1 only the "past the end" row i + 1 = K + 1 is)
-            if (k >= (band ? max(1, s_top - s + 1) : 1) && k <= K - s + 1 && d >= s) {
-                const int i_first = (s == 1) ? K : k, i_last = K - s + 1;
-                for (int i = i_first; i <= i_last; ++i) {
-                    const int32_t *tp = tab_s + ((size_t)(k - 1) * K + (i - 1)) * S;
-                    const int32_t *prow = prev + (i + 1) * (D + 1);
-                    for (int q = 0; q < S; ++q) {
-                        const int a = sizes[q];
-                        if (a > d) continue;
-                        const int32_t t = tp[q];
-                        if (t == INF_I32 || t > c) continue;
-                        const int32_t f = prow[d - a];
-                        if (f >= DEV_INF) continue;
-                        const int32_t sum = t + f;
-                        if (sum < v) v = sum;
-                    }
-                }
-            }
-            cur[x] = v;
+            cur[x] = relax_cell(p, tab_s, sizes, prev, c, s, k, d, 1);
         }
         __syncthreads();
         const int32_t f1 = cur[1 * (D + 1) + D];       // F(s, first layer, all devices)
@@ -86,7 +94,7 @@ __global__ __launch_bounds__(GENERIC_MAX_THREADS) void recurrence_generic_kernel
     Problem p, const int32_t *__restrict__ table, const int32_t *__restrict__ sizes,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
     int64_t *chunk_min, int prune, int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest,
-    int32_t *scratch, int n_layers, const int32_t *__restrict__ s_top_p)
+    int32_t *scratch, int n_layers)
 {
     __shared__ int32_t sh_tk[GENERIC_MAX_THREADS];
     __shared__ int sh_skip[WAVE];
@@ -117,14 +125,65 @@ __global__ __launch_bounds__(GENERIC_MAX_THREADS) void recurrence_generic_kernel
             }
         }
         int32_t best, sbest;
-        const int s_top = s_top_p ? min(p.Smax, *s_top_p) : p.Smax;
-        fill_layers(p, table, sizes, c, slot, n_layers, s_top, s_top_p != nullptr, &best, &sbest);
+        fill_layers(p, table, sizes, c, slot, n_layers, &best, &sbest);
         Fmin[j] = best;                           // all threads, same value
         Sbest[j] = best >= DEV_INF ? 0 : sbest;
         if (prune && best < DEV_INF)              // uniform; the minimum is idempotent
             atomicMin((long long *)&chunk_min[j / PRUNE_CHUNK],
                       (long long)best + (long long)(p.B - 1) * (long long)c);
         __syncthreads();
+    }
+}
+
+// Plan recovery, one launch per layer: layer s (0..Smax) of the one candidate *c_p into
+// F_all[s], every cell a thread, so that the whole device works on it (the single workgroup of
+// recurrence_generic_kernel takes tens of milliseconds at the larger sizes).  Does nothing if
+// *n_p == 0 (no winner) or s exceeds *s_top_p; only the cells the walk back from (s_top, first
+// layer 1) can reach are computed.
+__global__ __launch_bounds__(256) void plan_layer_kernel(
+    Problem p, const int32_t *__restrict__ table, const int32_t *__restrict__ sizes,
+    const int32_t *__restrict__ c_p, const int32_t *__restrict__ n_p,
+    const int32_t *__restrict__ s_top_p, int s, int32_t *__restrict__ F_all)
+{
+    if (*n_p <= 0) return;
+    const int s_top = min(p.Smax, *s_top_p);
+    if (s > s_top) return;
+    const int K = p.K, D = p.D, S = p.S;
+    const int LS = (K + 2) * (D + 1);
+    int32_t *cur = F_all + (size_t)s * LS;
+    if (s == 0) {                                  // only F(0, K+1, 0) = 0
+        for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < LS; x += gridDim.x * blockDim.x)
+            cur[x] = (x == (K + 1) * (D + 1)) ? 0 : DEV_INF;
+        return;
+    }
+    const int32_t c = *c_p;
+    const int32_t *prev = F_all + (size_t)(s - 1) * LS;
+    const int32_t *tab_s = table + (size_t)(s - 1) * K * K * S;
+    // a wave per cell, its lanes over the (last layer, shape) terms of the cell
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    const int k_min = max(1, s_top - s + 1);
+    for (int x = wave; x < LS; x += n_waves) {
+        const int k = x / (D + 1), d = x - k * (D + 1);
+        int32_t v = DEV_INF;
+        if (k >= k_min && k <= K - s + 1 && d >= s) {   // see relax_cell
+            const int i_first = (s == 1) ? K : k, i_last = K - s + 1;
+            const int n_terms = (i_last - i_first + 1) * S;
+            const int32_t *tp = tab_s + ((size_t)(k - 1) * K + (i_first - 1)) * S;
+            for (int j = lane; j < n_terms; j += WAVE) {
+                const int di = j / S, q = j - di * S;
+                const int a = sizes[q];
+                if (a > d) continue;
+                const int32_t t = tp[j];
+                if (t == INF_I32 || t > c) continue;
+                const int32_t f = prev[(i_first + di + 1) * (D + 1) + d - a];
+                if (f >= DEV_INF) continue;
+                v = min(v, t + f);
+            }
+        }
+        for (int off = 32; off >= 1; off >>= 1) v = min(v, __shfl_xor(v, off, 64));
+        if (lane == 0) cur[x] = v;
     }
 }
 
@@ -396,13 +455,24 @@ hipError_t launch_recurrence_generic(hipStream_t st, const Problem &p, const int
                                      const int32_t *sizes, const int32_t *cand,
                                      const int32_t *n_cand_p, int32_t *ticket, int64_t *chunk_min,
                                      int prune, int32_t *Fmin, int32_t *Sbest, int32_t *scratch,
-                                     int n_layers, int grid, const int32_t *s_top_p)
+                                     int n_layers, int grid)
 {
-    // a lone workgroup (the plan-recovery run of one candidate) gets the widest block
+    // a lone workgroup (a single candidate) gets the widest block
     const int threads = grid == 1 ? GENERIC_MAX_THREADS : 256;
     hipLaunchKernelGGL(recurrence_generic_kernel, dim3(grid), dim3(threads), 0, st, p, table, sizes,
-                       cand, n_cand_p, ticket, chunk_min, prune, Fmin, Sbest, scratch, n_layers,
-                       s_top_p);
+                       cand, n_cand_p, ticket, chunk_min, prune, Fmin, Sbest, scratch, n_layers);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_layers(hipStream_t st, const Problem &p, const int32_t *table,
+                              const int32_t *sizes, const int32_t *c_p, const int32_t *n_p,
+                              const int32_t *s_top_p, int32_t *F_all)
+{
+    const int LS = (p.K + 2) * (p.D + 1);
+    const int grid = std::min((LS + 3) / 4, 4096);     // four cells (waves) per block
+    for (int s = 0; s <= p.Smax; ++s)
+        hipLaunchKernelGGL(plan_layer_kernel, dim3(grid), dim3(256), 0, st, p, table, sizes, c_p,
+                           n_p, s_top_p, s, F_all);
     return hipGetLastError();
 }
 

@@ -97,6 +97,17 @@ _A2A_US = {1: 0, 2: 300, 4: 600, 8: 900, 16: 1200, 24: 1375, 32: 1500,
            40: 1597, 48: 1675, 56: 1742, 64: 1800}
 
 
+def _a2a_us(a: int) -> int:
+    """All-to-all time of one expert layer on a devices: the tabulated values (300 log2 a,
+    rounded) for the sizes of the 8 x 8 mesh, the same formula beyond."""
+    if a <= 1:
+        return 0
+    if a in _A2A_US:
+        return _A2A_US[a]
+    import math
+    return int(math.floor(300.0 * math.log2(a) + 0.5))
+
+
 def _formula_table(K, shapes, cost, mem, act_per_layer, cap, *, expert=None,
                    act_mode="const", terms=None):
     """t(k..i, q, s) = ceil(sum c / a) + 50 (a - 1) + (n > 1 ? 400 : 0) [+ experts * a2a(a)],
@@ -116,7 +127,7 @@ def _formula_table(K, shapes, cost, mem, act_per_layer, cap, *, expert=None,
     if expert is not None:
         pe = np.concatenate([[0], np.cumsum(expert.astype(np.int64))])
         ecnt = np.where(valid, pe[ii + 1] - pe[kk], 0)
-        a2a = np.asarray([_A2A_US[int(x)] if x > 1 else 0 for x in a], dtype=np.int64)
+        a2a = np.asarray([_a2a_us(int(x)) for x in a], dtype=np.int64)
         lat = lat + ecnt[:, :, None] * a2a[None, None, :]
     if act_mode == "const":
         actv = np.full((K, K), int(act_per_layer), dtype=np.int64)
