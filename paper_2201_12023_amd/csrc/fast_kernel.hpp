@@ -1,5 +1,7 @@
 // Register/LDS recurrence kernel (Eq. 3) for K <= 128 layers on N*M <= 64 devices, and on up
-// to 128 devices in a two-window form (see WIDE below).
+// to 128 devices in a two-window form (see WIDE below).  A header: the instances for up to 64
+// and for 65-128 layers are compiled in two translation units (kernels_fast.hip,
+// kernels_fast_deep.hip).
 //
 // Mapping.  One workgroup evaluates one t_max candidate at a time (persistent workgroups
 // draw candidates from a ticket counter).  Lane l of every wave owns device count
@@ -26,7 +28,6 @@
 //    first layer is > i or >= K or the entry is +infinity}.
 // The array is padded by a few records so that the one-column-ahead loads may run past the
 // last column.
-#include "internal.hpp"
 #pragma once
 #include "internal.hpp"
 
