@@ -138,8 +138,17 @@ __global__ __launch_bounds__(256) void valu_peak_kernel(int iters, Scalars16 sv,
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int rep = 0; rep < 8; ++rep) {
+            // the sixteen sums (distinct scalar operands) before the sixteen minima, as the
+            // recurrence kernel orders them: a minimum right behind its own sum holds the wave up
+            int32_t sum[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) a[u] = min(a[u], sv.v[u] + g);   // 16 distinct scalar operands
+            for (int u = 0; u < 16; ++u) sum[u] = sv.v[u] + g;
+            asm volatile("" : "+v"(sum[0]), "+v"(sum[1]), "+v"(sum[2]), "+v"(sum[3]), "+v"(sum[4]),
+                              "+v"(sum[5]), "+v"(sum[6]), "+v"(sum[7]), "+v"(sum[8]), "+v"(sum[9]),
+                              "+v"(sum[10]), "+v"(sum[11]), "+v"(sum[12]), "+v"(sum[13]),
+                              "+v"(sum[14]), "+v"(sum[15]));
+#pragma unroll
+            for (int u = 0; u < 16; ++u) a[u] = min(a[u], sum[u]);
             // "everything may have changed": no repetition is folded away or fused with the next
             asm volatile("" : "+v"(g), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]),
                               "+v"(a[5]), "+v"(a[6]), "+v"(a[7]), "+v"(a[8]), "+v"(a[9]),
