@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy a few times, so that a counter "
                          "run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
-    ap.add_argument("--traffic-bytes", type=float, default=49.1e6,
+    ap.add_argument("--traffic-bytes", type=float, default=50.0e6,
                     help="measured HBM bytes per launch of the recurrence kernel, reported as "
                          "roofline.traffic; the default is the stored measurement for workload 4 "
                          "(two rocprofv3 --pmc runs, profiles/recurrence_fast_kernel_workload4_"
