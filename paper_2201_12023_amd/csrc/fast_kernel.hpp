@@ -110,16 +110,9 @@ __device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)
             }
             if (COUNT) ++n_blocks;
             relax_update(acc[e], off, t, G[e]);
-            // The next candidate filters the same eight registers in place; pinning them here
-            // keeps the two update sequences apart (merged, they need a second copy of the
-            // values, i.e. eight scalar moves per half-block).
-            if (e > 0)
-                asm volatile("" : "+s"(t[0]), "+s"(t[1]), "+s"(t[2]), "+s"(t[3]), "+s"(t[4]),
-                                  "+s"(t[5]), "+s"(t[6]), "+s"(t[7]), "+v"(acc[e][off + 0]),
-                                  "+v"(acc[e][off + 1]), "+v"(acc[e][off + 2]),
-                                  "+v"(acc[e][off + 3]), "+v"(acc[e][off + 4]),
-                                  "+v"(acc[e][off + 5]), "+v"(acc[e][off + 6]),
-                                  "+v"(acc[e][off + 7]));
+            // (the next candidate filters the same eight registers in place: the compiler puts
+            // its selects between this candidate's sums and minima)
+            if (e > 0) asm volatile("" ::: "memory");
         }
     }
 }
