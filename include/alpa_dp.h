@@ -141,8 +141,22 @@ int alpa_dp_get_table(alpa_dp_t *h, int32_t *out_table);
  * cuda_stream field of a torch.cuda.Stream).  The caller keeps the stream alive. */
 int alpa_dp_set_stream(alpa_dp_t *h, void *hip_stream);
 
-/* Change B (Sec. 7: B is a hyper-parameter searched by enumeration).  B >= 1. */
+/* Change B (Sec. 7: B is a hyper-parameter searched by enumeration).  B >= 1.  T* of Eq. 4
+ * under different B do not compare, so a change of B resets the running best of alpa_dp_best
+ * (which is then the best over the solves made since).  Errors: EINVAL, EHIP. */
 int alpa_dp_set_B(alpa_dp_t *h, int B);
+
+/*
+ * Tuning of the launch shape; cites no passage of the paper because no result depends on it
+ * (the parity tests run every setting against the same oracle values).  value 0 restores the
+ * library's own choice.  Errors: EINVAL (null handle, unknown key, value out of range).
+ */
+#define ALPA_DP_TUNE_CANDIDATES_PER_WG 1  /* 1 or 2 t_max candidates per workgroup of the
+                                             register/LDS kernel (own choice: 2 for long lists)  */
+#define ALPA_DP_TUNE_DISTINCT_BY_SORT  2  /* 1: distinct table values by the radix sort also where
+                                             the presence bitmap applies                        */
+#define ALPA_DP_TUNE_WG_PER_CU         3  /* upper bound on resident workgroups per compute unit */
+int alpa_dp_set_tuning(alpa_dp_t *h, int key, int value);
 
 /* Number of distinct finite values of the table (entries with i >= k): the length
  * of Alg. 1's "SortedAndFilter(t_intra, epsilon)" list for integer latencies and
@@ -212,9 +226,10 @@ int alpa_dp_solve_sweep(alpa_dp_t *h, const int32_t *tmax, int n_tmax, unsigned 
  * `cap` values to the HOST array `out` and stores the count in *out_n.  Blocking. */
 int alpa_dp_candidates(alpa_dp_t *h, int32_t *out, int cap, int *out_n);
 
-/* Best plan over every solve made on the handle so far (lowest T*, then lowest t_max);
- * if none was made, runs alpa_dp_solve(h, NULL, 0, ALPA_DP_PRUNE, NULL, out_plan)
- * first ("the minimal pipeline execution latency T*" that Alg. 1 outputs).  Blocking. */
+/* Best plan over every alpa_dp_solve / alpa_dp_solve_dev made on the handle with its present
+ * table and B (lowest T*, then lowest t_max); sweeps do not count.  If there was none, runs
+ * alpa_dp_solve(h, NULL, 0, ALPA_DP_PRUNE, NULL, out_plan) first ("the minimal pipeline
+ * execution latency T*" that Alg. 1 outputs).  Blocking. */
 int alpa_dp_best(alpa_dp_t *h, alpa_plan_t *out_plan);
 
 /* Device time of the phases of the last solve, from HIP events recorded on the
@@ -284,7 +299,7 @@ int alpa_place_submeshes(int N, int M, const alpa_shape_t *stage_shapes, int num
                          int32_t *out_row, int32_t *out_col);
 
 /*
- * Measurement aid: sustained rate of the recurrence's two vector instructions (int32 add with a
+ * Measurement aid, outside the method's boundary (no step of the paper): sustained rate of the recurrence's two vector instructions (int32 add with a
  * scalar operand, signed min) from a register-only kernel at full occupancy on the current
  * device, in lane-operations per second, to set beside the nominal peak (compute units x 64
  * lanes x clock).  Blocking, about 50 ms.  Errors: EINVAL (null pointer), EHIP.

@@ -24,9 +24,12 @@ INF_I64 = 2**63 - 1
 ALPA_DP_PRUNE = 1
 ALPA_DP_GENERIC = 2
 ALPA_DP_COUNT_WORK = 4
+ALPA_DP_TUNE_CANDIDATES_PER_WG = 1
+ALPA_DP_TUNE_DISTINCT_BY_SORT = 2
+ALPA_DP_TUNE_WG_PER_CU = 3
 
 SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table",
-           "alpa_dp_restrict_equal_layers", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_count_candidates",
+           "alpa_dp_restrict_equal_layers", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_set_tuning", "alpa_dp_count_candidates",
            "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
            "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
@@ -84,6 +87,7 @@ def load():
     L.alpa_dp_restrict_equal_layers.argtypes = [vp]
     L.alpa_dp_set_stream.argtypes = [vp, vp]
     L.alpa_dp_set_B.argtypes = [vp, ctypes.c_int]
+    L.alpa_dp_set_tuning.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     L.alpa_dp_count_candidates.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]
     L.alpa_dp_solve.argtypes = [vp, vp, ctypes.c_int, ctypes.c_uint, vp, vp]
     L.alpa_dp_solve_dev.argtypes = [vp, vp, ctypes.c_int, ctypes.c_uint, vp, vp]
@@ -161,6 +165,10 @@ def alpa_dp_set_stream(h, stream):
 
 def alpa_dp_set_B(h, B):
     _check(load().alpa_dp_set_B(h, int(B)))
+
+
+def alpa_dp_set_tuning(h, key, value):
+    _check(load().alpa_dp_set_tuning(h, int(key), int(value)))
 
 
 def alpa_dp_count_candidates(h) -> int:

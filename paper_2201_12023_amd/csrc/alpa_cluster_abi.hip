@@ -101,29 +101,3 @@ extern "C" int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *ed
     if (out_ms) HIPCHK(hipEventElapsedTime(out_ms, ev0, ev1));
     return ALPA_DP_OK;
 }
-
-extern "C" int alpa_dp_measure_valu_peak(double *out_lane_ops_per_s)
-{
-    if (!out_lane_ops_per_s) return fail(ALPA_DP_EINVAL, "null argument");
-    hipDeviceProp_t prop;
-    int dev = 0;
-    HIPCHK(hipGetDevice(&dev));
-    HIPCHK(hipGetDeviceProperties(&prop, dev));
-    DevBuf sink;
-    HIPCHK(sink.alloc(64));
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    HIPCHK(hipEventCreate(&ev0));
-    HIPCHK(hipEventCreate(&ev1));
-    struct EvGuard { hipEvent_t a, b; ~EvGuard() { (void)hipEventDestroy(a); (void)hipEventDestroy(b); } }
-        guard{ev0, ev1};
-    const int grid = prop.multiProcessorCount * 8, iters = 4000;       // 8 waves per SIMD
-    HIPCHK(launch_valu_peak(nullptr, grid, 100, sink.as<int32_t>()));  // warm-up
-    HIPCHK(hipEventRecord(ev0, nullptr));
-    HIPCHK(launch_valu_peak(nullptr, grid, iters, sink.as<int32_t>()));
-    HIPCHK(hipEventRecord(ev1, nullptr));
-    HIPCHK(hipEventSynchronize(ev1));
-    float ms = 0;
-    HIPCHK(hipEventElapsedTime(&ms, ev0, ev1));
-    *out_lane_ops_per_s = (double)grid * 256.0 * 256.0 * iters / (ms * 1e-3);
-    return ALPA_DP_OK;
-}

@@ -5,7 +5,6 @@
 
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -70,7 +69,11 @@ struct alpa_dp {
     alpa_plan_t *d_sw_plans = nullptr;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     bool any_solve = false, timed = false;
-    int last_host_n = 0;
+    bool have_best = false;         // d_best_plan holds the best of a solve made with the current
+                                    // table and B (sweeps do not touch it)
+    // tuning (alpa_dp_set_tuning); 0 = the library's own choice
+    int tune_nc = 0, tune_sort = 0, tune_wg_per_cu = 0;
+    int fast_per_cu[3] = {0, 0, 0};  // resident workgroups per compute unit, [nc]
 };
 
 static void free_candidate_arrays(alpa_dp *h)
@@ -83,28 +86,49 @@ static void free_candidate_arrays(alpa_dp *h)
     h->d_cand = h->d_rank = h->d_tmax_stage = h->d_Fmin = h->d_Sbest = h->d_distinct = nullptr;
     h->d_T = h->d_outT_stage = h->d_chunkmin = nullptr;
     h->cand_cap = 0;
+    h->pb.cap = 0;
 }
 
-// Per-candidate arrays for up to `cap` keys / candidates.
+// Per-candidate arrays for up to `cap` keys / candidates.  All or nothing: after a failure
+// every pointer is null and both capacities are 0, so the next solve tries again (and fails
+// with ENOMEM again rather than launching on short buffers).
 static int alloc_candidate_arrays(alpa_dp *h, int cap)
 {
     free_candidate_arrays(h);
     const size_t c = (size_t)cap;
-    HIPCHK(hipMalloc(&h->pb.keys[0], c * 4));
-    HIPCHK(hipMalloc(&h->pb.keys[1], c * 4));
-    HIPCHK(hipMalloc(&h->pb.block_cnt, (c / 4096 + 2) * 4));
-    HIPCHK(hipMalloc(&h->d_distinct, c * 4));
-    HIPCHK(hipMalloc(&h->d_cand, c * 4));
-    HIPCHK(hipMalloc(&h->d_rank, c * 4));
-    HIPCHK(hipMalloc(&h->d_tmax_stage, c * 4));
-    HIPCHK(hipMalloc(&h->d_Fmin, (c + 1) * 4));      // + one spare slot (see FastArgs)
-    HIPCHK(hipMalloc(&h->d_Sbest, (c + 1) * 4));
-    HIPCHK(hipMalloc(&h->d_T, c * 8));
-    HIPCHK(hipMalloc(&h->d_outT_stage, c * 8));
-    HIPCHK(hipMalloc(&h->d_chunkmin, (c / PRUNE_CHUNK + 2) * 8));
+    auto body = [&]() -> int {
+        HIPCHK(hipMalloc(&h->pb.keys[0], c * 4));
+        HIPCHK(hipMalloc(&h->pb.keys[1], c * 4));
+        HIPCHK(hipMalloc(&h->pb.block_cnt, (c / 4096 + 2) * 4));
+        HIPCHK(hipMalloc(&h->d_distinct, c * 4));
+        HIPCHK(hipMalloc(&h->d_cand, c * 4));
+        HIPCHK(hipMalloc(&h->d_rank, c * 4));
+        HIPCHK(hipMalloc(&h->d_tmax_stage, c * 4));
+        HIPCHK(hipMalloc(&h->d_Fmin, (c + 1) * 4));      // + one spare slot (see FastArgs)
+        HIPCHK(hipMalloc(&h->d_Sbest, (c + 1) * 4));
+        HIPCHK(hipMalloc(&h->d_T, c * 8));
+        HIPCHK(hipMalloc(&h->d_outT_stage, c * 8));
+        HIPCHK(hipMalloc(&h->d_chunkmin, (c / PRUNE_CHUNK + 2) * 8));
+        return ALPA_DP_OK;
+    };
+    const int rc = body();
+    if (rc != ALPA_DP_OK) {
+        free_candidate_arrays(h);
+        return rc;
+    }
     h->pb.cap = cap;
     h->cand_cap = cap;
     return ALPA_DP_OK;
+}
+
+// Capacity every solve needs: the table's keys for the sort of its values, and the caller's
+// list if that is longer.
+static int ensure_candidate_arrays(alpa_dp *h, int n_list)
+{
+    const int need = std::max(std::max(h->n_table_keys, 1024), n_list);
+    if (h->cand_cap >= need) return ALPA_DP_OK;
+    HIPCHK(hipStreamSynchronize(h->stream));
+    return alloc_candidate_arrays(h, need);
 }
 
 static void free_sweep_arrays(alpa_dp *h)
@@ -149,7 +173,7 @@ static int bits_for(uint32_t v)
 static int queue_table_candidates(alpa_dp *h)
 {
     // small values: one bit per value instead of a sort (the second key buffer is the work area)
-    if (h->max_finite >= 0 && h->max_finite < DISTINCT_BITMAP_MAX && !getenv("ALPA_DP_SORT") &&
+    if (h->max_finite >= 0 && h->max_finite < DISTINCT_BITMAP_MAX && !h->tune_sort &&
         distinct_bitmap_words(h->max_finite) <= (size_t)h->pb.cap) {
         HIPCHK(launch_distinct_by_bitmap(h->stream, h->d_table, h->p.K, h->p.S, h->max_finite,
                                          (uint32_t *)h->pb.keys[1], h->d_distinct,
@@ -258,14 +282,11 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
         for (int nc = 1; nc <= 2; ++nc) {
             int per_cu = fast_kernel_blocks_per_cu(K, nc);
             if (per_cu < 1) return fail(ALPA_DP_EHIP, "fast kernel does not fit on a CU");
-            if (const char *e = getenv("ALPA_DP_WG_PER_CU")) {   // tuning aid
-                const int v = atoi(e);
-                if (v >= 1 && v < per_cu) per_cu = v;
-            }
+            h->fast_per_cu[nc] = per_cu;
             h->fast_grid_max[nc] = h->n_cu * per_cu;
         }
     }
-    int rc2 = alloc_candidate_arrays(h, std::max(h->n_table_keys, 1024));
+    int rc2 = ensure_candidate_arrays(h, 0);
     if (rc2) return rc2;
     // length of the full candidate list
     rc2 = queue_table_candidates(h);
@@ -306,25 +327,25 @@ extern "C" int alpa_dp_create(alpa_dp_t **out, const int32_t *cost_table, int K,
     int rc = check_problem(K, N, M, B, shapes, num_shapes, sizes);
     if (rc) return rc;
     const int S = num_shapes;
-    // range check of the part of the table that is used
-    int32_t max_finite = -1;
-    for (int s = 0; s < K; ++s)
-        for (int k = 0; k < K; ++k) {
-            const int32_t *row = cost_table + (((size_t)s * K + k) * K + k) * S;
-            const size_t cnt = (size_t)(K - k) * S;
-            for (size_t x = 0; x < cnt; ++x) {
-                const int32_t t = row[x];
-                if (t < 0) return fail(ALPA_DP_EINVAL, "negative latency in cost_table");
-                if (t != ALPA_DP_INF_I32 && t > max_finite) max_finite = t;
-            }
-        }
-    if (max_finite >= 0 && (long long)K * max_finite >= (1ll << 30))
-        return fail(ALPA_DP_EOVERFLOW, "K * largest finite latency >= 2^30");
     return create_handle(out, K, N, M, B, sizes, [&](alpa_dp *h) -> int {
-        h->max_finite = max_finite;
-        HIPCHK(hipMemcpyAsync(h->d_table, cost_table, (size_t)K * K * K * S * 4,
-                              hipMemcpyHostToDevice, h->stream));
-        return ALPA_DP_OK;
+        // the range check of the used part of the table (no negative latency; largest finite
+        // entry for the overflow proof) is a reduction on the device copy
+        int32_t *d_range = nullptr;
+        auto body = [&]() -> int {
+            HIPCHK(hipMalloc(&d_range, 2 * 4));
+            HIPCHK(hipMemcpyAsync(h->d_table, cost_table, (size_t)K * K * K * S * 4,
+                                  hipMemcpyHostToDevice, h->stream));
+            HIPCHK(launch_table_range(h->stream, h->d_table, K, S, d_range));
+            int32_t range[2] = {0, -1};
+            HIPCHK(hipMemcpyAsync(range, d_range, sizeof(range), hipMemcpyDeviceToHost, h->stream));
+            HIPCHK(hipStreamSynchronize(h->stream));
+            if (range[0] < 0) return fail(ALPA_DP_EINVAL, "negative latency in cost_table");
+            h->max_finite = range[1];
+            return ALPA_DP_OK;
+        };
+        const int rc2 = body();
+        (void)hipFree(d_range);
+        return rc2;
     });
 }
 
@@ -405,6 +426,7 @@ extern "C" int alpa_dp_restrict_equal_layers(alpa_dp_t *h)
     HIPCHK(hipStreamSynchronize(h->stream));
     h->n_distinct = (int)nd;
     h->any_solve = false;
+    h->have_best = false;
     return ALPA_DP_OK;
 }
 
@@ -434,8 +456,42 @@ extern "C" int alpa_dp_set_B(alpa_dp_t *h, int B)
 {
     if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
     if (B < 1) return fail(ALPA_DP_EINVAL, "B must be >= 1");
+    if (B == h->p.B) return ALPA_DP_OK;
+    // T* of Eq. 4 under different B values do not compare: the running best starts over
+    int prev = 0;
+    HIPCHK(hipGetDevice(&prev));
+    if (prev != h->device) HIPCHK(hipSetDevice(h->device));
+    struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
+        restore{prev, h->device};
+    HIPCHK(launch_init_best_plan(h->stream, h->d_best_plan));
+    h->have_best = false;
     h->p.B = B;
     return ALPA_DP_OK;
+}
+
+extern "C" int alpa_dp_set_tuning(alpa_dp_t *h, int key, int value)
+{
+    if (!h) return fail(ALPA_DP_EINVAL, "handle is null");
+    switch (key) {
+    case ALPA_DP_TUNE_CANDIDATES_PER_WG:
+        if (value < 0 || value > 2) return fail(ALPA_DP_EINVAL, "candidates per workgroup: 0, 1 or 2");
+        h->tune_nc = value;
+        return ALPA_DP_OK;
+    case ALPA_DP_TUNE_DISTINCT_BY_SORT:
+        if (value < 0 || value > 1) return fail(ALPA_DP_EINVAL, "distinct values by sort: 0 or 1");
+        h->tune_sort = value;
+        return ALPA_DP_OK;
+    case ALPA_DP_TUNE_WG_PER_CU:
+        if (value < 0) return fail(ALPA_DP_EINVAL, "workgroups per compute unit: >= 0");
+        h->tune_wg_per_cu = value;
+        for (int nc = 1; nc <= 2; ++nc) {
+            const int per_cu = (value >= 1 && value < h->fast_per_cu[nc]) ? value : h->fast_per_cu[nc];
+            h->fast_grid_max[nc] = h->n_cu * per_cu;
+        }
+        return ALPA_DP_OK;
+    default:
+        return fail(ALPA_DP_EINVAL, "unknown tuning key");
+    }
 }
 
 extern "C" int alpa_dp_count_candidates(alpa_dp_t *h, int *out_n)
@@ -468,9 +524,8 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (prev != h->device) HIPCHK(hipSetDevice(h->device));
     struct Restore { int prev, cur; ~Restore() { if (prev != cur) (void)hipSetDevice(prev); } }
         restore{prev, h->device};
-    if (have_list && n_tmax > h->cand_cap) {
-        HIPCHK(hipStreamSynchronize(h->stream));
-        int rc = alloc_candidate_arrays(h, n_tmax);
+    {
+        const int rc = ensure_candidate_arrays(h, have_list ? n_tmax : 0);
         if (rc) return rc;
     }
     const int bound = candidate_bound(h, have_list, n_tmax);
@@ -503,7 +558,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             // two candidates per workgroup share every scalar load; worth it once there are
             // enough candidates to fill the device twice over that way
             int nc = (bound >= 4 * h->fast_grid_max[2]) ? 2 : 1;
-            if (const char *e = getenv("ALPA_DP_NC")) nc = atoi(e) == 2 ? 2 : 1;   // tuning aid
+            if (h->tune_nc) nc = h->tune_nc;
             const bool wide = p.D > 64;            // two windows of device counts, one candidate
             if (wide) nc = 2;
             const int per_wg = wide ? 1 : nc;
@@ -568,6 +623,7 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
                             h->d_best_plan, d_out_plan));
     HIPCHK(hipEventRecord(h->ev[3], st));
     h->any_solve = true;
+    h->have_best = true;
     h->timed = true;
     return ALPA_DP_OK;
 }
@@ -595,9 +651,8 @@ static int stage_host_candidates(alpa_dp *h, const int32_t *tmax, int n_tmax,
             mx = std::max(mx, tmax[j]);
         }
         *key_bits = bits_for((uint32_t)mx);
-        if (n_tmax > h->cand_cap) {
-            HIPCHK(hipStreamSynchronize(h->stream));
-            int rc = alloc_candidate_arrays(h, n_tmax);
+        {
+            const int rc = ensure_candidate_arrays(h, n_tmax);
             if (rc) return rc;
         }
         HIPCHK(hipMemcpyAsync(h->d_tmax_stage, tmax, (size_t)n_tmax * 4, hipMemcpyHostToDevice,
@@ -666,7 +721,10 @@ extern "C" int alpa_dp_solve_sweep(alpa_dp_t *h, const int32_t *tmax, int n_tmax
     HIPCHK(hipMemcpyAsync(h->d_sw_n, head, sizeof(head), hipMemcpyHostToDevice, h->stream));
     HIPCHK(hipMemcpyAsync(h->d_sw_B, B_values, (size_t)n_B * 4, hipMemcpyHostToDevice, h->stream));
     rc = solve_dev_impl(h, d_tmax, n_tmax, flags, nullptr, nullptr, key_bits, n_B);
-    if (rc) return rc;
+    if (rc) {
+        (void)hipStreamSynchronize(h->stream);     // `head` above is read by a queued copy
+        return rc;
+    }
     HIPCHK(hipMemcpyAsync(out_plans, h->d_sw_plans, (size_t)n_B * sizeof(alpa_plan_t),
                           hipMemcpyDeviceToHost, h->stream));
     HIPCHK(hipStreamSynchronize(h->stream));
@@ -700,7 +758,7 @@ extern "C" int alpa_dp_candidates(alpa_dp_t *h, int32_t *out, int cap, int *out_
 extern "C" int alpa_dp_best(alpa_dp_t *h, alpa_plan_t *out_plan)
 {
     if (!h || !out_plan) return fail(ALPA_DP_EINVAL, "null argument");
-    if (!h->any_solve) {
+    if (!h->have_best) {
         int rc = alpa_dp_solve(h, nullptr, 0, ALPA_DP_PRUNE, nullptr, nullptr);
         if (rc) return rc;
     }

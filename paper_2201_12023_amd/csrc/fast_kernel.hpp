@@ -233,17 +233,20 @@ void recurrence_fast_kernel(
         if (tk >= n_groups) break;                     // the workgroup's only exit
         const int j0 = (descending ? (n_groups - 1 - tk) : tk) * NCAND;
         int jj[NC];                                    // candidate indices (the last may repeat;
-        int32_t c[NC];                                 //  both windows serve one candidate)
+        int32_t c[NC], c_given[NC];                    //  both windows serve one candidate)
 #pragma unroll
         for (int e = 0; e < NC; ++e) {
             jj[e] = WIDE ? j0 : min(j0 + e, n - 1);
-            c[e] = __builtin_amdgcn_readfirstlane(cand[jj[e]]);
+            c_given[e] = __builtin_amdgcn_readfirstlane(cand[jj[e]]);
+            // as a filter every value from DEV_INF on is "no filter" (finite entries are far
+            // below); clamped so that the sentinel entries themselves never pass it
+            c[e] = min(c_given[e], DEV_INF - 1);
         }
         if (prune) {
             // If the lowest candidate of the group may be skipped so may the others (their
             // evidence set is a superset and B * t_max is larger).  Wave 0's reading of the
             // published minima decides for the whole workgroup.
-            sh_skip[wid] = can_skip_fast(chunk_min, jj[0], c[0], p.B, lane) ? 1 : 0;
+            sh_skip[wid] = can_skip_fast(chunk_min, jj[0], c_given[0], p.B, lane) ? 1 : 0;
             __syncthreads();
             const int skip = __builtin_amdgcn_readfirstlane(sh_skip[0]);
             __syncthreads();
@@ -583,7 +586,7 @@ void recurrence_fast_kernel(
             Sbest[slot] = bestD >= DEV_INF ? 0 : sD;
             if (prune) {                               // uniform; the minimum is idempotent
                 const long long T = (owner && bestD < DEV_INF)
-                                        ? (long long)bestD + (long long)(p.B - 1) * (long long)c[e]
+                                        ? (long long)bestD + (long long)(p.B - 1) * (long long)c_given[e]
                                         : (long long)INF_I64;
                 atomicMin((long long *)&chunk_min[jj[e] / PRUNE_CHUNK], T);
             }

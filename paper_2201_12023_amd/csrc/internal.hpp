@@ -142,6 +142,9 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
                               const int64_t *mem_act, int K, int S, int O, int64_t mem_device,
                               int32_t *table, int32_t *max_finite);
 
+// out[0] = smallest, out[1] = largest finite entry (-1 if none) of the used part of a table
+hipError_t launch_table_range(hipStream_t st, const int32_t *table, int K, int S, int32_t *out);
+
 hipError_t launch_valu_peak(hipStream_t st, int grid, int iters, int32_t *sink);
 hipError_t launch_equal_layer_mask(hipStream_t st, int32_t *table, int K, int S);
 

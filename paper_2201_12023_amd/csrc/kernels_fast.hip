@@ -50,7 +50,8 @@ __global__ void repack_group_min_kernel(int K, int S, int KP, int SW, const int3
         const int hb = (e / SW) % NHB;
         const int q = e / (SW * NHB);
         const int GW = end_group_cols(KP);
-        int32_t run = 0x3f3f3f3f;                      // above DEV_INF: never alive
+        int32_t run = DEV_INF;                         // no entry: alive for no candidate (the
+                                                       // kernel clamps candidates below DEV_INF)
         for (int j = END_GROUPS - 1; j >= 0; --j) {
             if (s1 < K)
                 for (int i = min(K, GW * j + GW) - 1; i >= GW * j; --i)

@@ -104,6 +104,42 @@ __global__ void set_i32_kernel(int32_t *p, int32_t v)
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
 }
 
+// Range of the part of a caller's table that the method reads (last layer >= first layer):
+// out[0] = smallest entry (a negative one is an argument error), out[1] = largest finite entry
+// (-1 if none; for the overflow proof and the sort's key width).  HBM-bound: 4 bytes per entry.
+__global__ __launch_bounds__(256) void table_range_kernel(const int32_t *__restrict__ table, int K,
+                                                          int S, int32_t *__restrict__ out)
+{
+    const long long total = (long long)K * K * K * S;
+    int32_t mn = INF_I32, mx = -1;
+    for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        long long r = e / S;
+        const int i = (int)(r % K); r /= K;
+        const int k = (int)(r % K);
+        if (i < k) continue;
+        const int32_t t = table[e];
+        mn = min(mn, t);
+        if (t != INF_I32) mx = max(mx, t);
+    }
+    mn = wave_min_i32(mn);
+    mx = -wave_min_i32(-mx);
+    if ((threadIdx.x & (WAVE - 1)) == 0) {
+        atomicMin(&out[0], mn);
+        atomicMax(&out[1], mx);
+    }
+}
+
+hipError_t launch_table_range(hipStream_t st, const int32_t *table, int K, int S, int32_t *out)
+{
+    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(WAVE), 0, st, out + 0, INF_I32);
+    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(WAVE), 0, st, out + 1, -1);
+    const long long total = (long long)K * K * K * S;
+    const int grid = (int)std::min<long long>((total + 255) / 256, 2048);
+    hipLaunchKernelGGL(table_range_kernel, dim3(grid), dim3(256), 0, st, table, K, S, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t *mem_stage,
                               const int64_t *mem_act, int K, int S, int O, int64_t mem_device,
                               int32_t *table, int32_t *max_finite)
@@ -114,62 +150,6 @@ hipError_t launch_build_table(hipStream_t st, const int32_t *t_l, const int64_t 
     const size_t lds = (size_t)O * TABLE_BLOCK * 2 * sizeof(int32_t);
     hipLaunchKernelGGL(build_table_kernel, dim3(grid), dim3(TABLE_BLOCK), lds, st, t_l, mem_stage,
                        mem_act, K, S, O, mem_device, table, max_finite);
-    return hipGetLastError();
-}
-
-}  // namespace alpa
-
-// ---------------------------------------------------------------- VALU peak probe
-
-// Register-only add + min chains (the two vector instructions of one cell-update, the add with
-// a scalar operand as in the recurrence kernel) at full occupancy: what the int32 vector ALU
-// can sustain, to set beside the nominal 256 CU x 64 lanes x clock figure.
-namespace alpa {
-
-struct Scalars16 { int32_t v[16]; };
-
-__global__ __launch_bounds__(256) void valu_peak_kernel(int iters, Scalars16 sv,
-                                                        int32_t *__restrict__ sink)
-{
-    int32_t a[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) a[u] = DEV_INF - (int)threadIdx.x - u;
-    int32_t g = (int32_t)threadIdx.x;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int rep = 0; rep < 8; ++rep) {
-            // the sixteen sums (distinct scalar operands) before the sixteen minima, as the
-            // recurrence kernel orders them: a minimum right behind its own sum holds the wave up
-            int32_t sum[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) sum[u] = sv.v[u] + g;
-            asm volatile("" : "+v"(sum[0]), "+v"(sum[1]), "+v"(sum[2]), "+v"(sum[3]), "+v"(sum[4]),
-                              "+v"(sum[5]), "+v"(sum[6]), "+v"(sum[7]), "+v"(sum[8]), "+v"(sum[9]),
-                              "+v"(sum[10]), "+v"(sum[11]), "+v"(sum[12]), "+v"(sum[13]),
-                              "+v"(sum[14]), "+v"(sum[15]));
-#pragma unroll
-            for (int u = 0; u < 16; ++u) a[u] = min(a[u], sum[u]);
-            // "everything may have changed": no repetition is folded away or fused with the next
-            asm volatile("" : "+v"(g), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]),
-                              "+v"(a[5]), "+v"(a[6]), "+v"(a[7]), "+v"(a[8]), "+v"(a[9]),
-                              "+v"(a[10]), "+v"(a[11]), "+v"(a[12]), "+v"(a[13]), "+v"(a[14]),
-                              "+v"(a[15]));
-        }
-        g = a[it & 15] ^ g;                       // keeps the chain from being folded
-        asm volatile("" : "+v"(g));
-    }
-    int32_t r = g;
-#pragma unroll
-    for (int u = 0; u < 16; ++u) r = min(r, a[u]);
-    if (r == 0x12345678) sink[0] = r;             // never true in practice; keeps the work alive
-}
-
-// 256 add/min instructions per iteration and thread are counted (the two chain-breaking ones not)
-hipError_t launch_valu_peak(hipStream_t st, int grid, int iters, int32_t *sink)
-{
-    Scalars16 sv;
-    for (int u = 0; u < 16; ++u) sv.v[u] = 3 + 2 * u;
-    hipLaunchKernelGGL(valu_peak_kernel, dim3(grid), dim3(256), 0, st, iters, sv, sink);
     return hipGetLastError();
 }
 

@@ -59,12 +59,7 @@ def test_create_rejects_bad_arguments_on_the_host():
     assert _create_rc(t, w.K, w.N, w.M, w.B, bad)[0] == -1
     bad = w.shapes.copy(); bad[2] = (1, 8)                               # larger than the mesh
     assert _create_rc(t, w.K, w.N, w.M, w.B, bad)[0] == -1
-    neg = t.copy(); neg[0, 0, 0, 0] = -5
-    assert _create_rc(neg, w.K, w.N, w.M, w.B, w.shapes)[0] == -1
-    # entries below the diagonal are not part of the problem and are not checked
-    big = t.copy(); big[big != W.INF_I32] = 2**30 // w.K
-    rc, msg = _create_rc(big, w.K, w.N, w.M, w.B, w.shapes)
-    assert rc == -2 and "2^30" in msg
+    # (the range of the table's values is checked by a reduction on the device: GPU tests)
 
 
 def test_null_handle_is_rejected():

@@ -36,7 +36,7 @@ def _problem(rng):
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
-def test_tuned_kernel_against_general_kernel(seed, monkeypatch):
+def test_tuned_kernel_against_general_kernel(seed):
     rng = np.random.default_rng(seed)
     for case in range(100):
         w = _problem(rng)
@@ -52,10 +52,8 @@ def test_tuned_kernel_against_general_kernel(seed, monkeypatch):
             else:
                 hi = int(w.table[w.table != W.INF_I32].max(initial=5)) + 3
                 args = (rng.integers(0, hi, size=int(rng.integers(1, 400))).astype(np.int32),)
-            if rng.integers(3) == 0:
-                monkeypatch.setenv("ALPA_DP_NC", "2")
-            else:
-                monkeypatch.delenv("ALPA_DP_NC", raising=False)
+            B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_CANDIDATES_PER_WG,
+                                 2 if rng.integers(3) == 0 else 0)
             T1, p1 = B.alpa_dp_solve(h, *args, flags=prune)
             T2, p2 = B.alpa_dp_solve(h, *args, flags=prune | B.ALPA_DP_GENERIC)
             what = f"seed {seed} case {case}: {w.name} K={w.K} {w.N}x{w.M} B={w.B} mode {mode} prune {prune}"

@@ -203,6 +203,15 @@ def test_best_over_several_solves_and_set_B():
         T, plan = B.alpa_dp_solve(h, None, 0, B.ALPA_DP_PRUNE)
         assert (T == T_ref).all()
         _same_plan(plan, p_ref)
+        # T* under B = 32 and under B = 3 do not compare: the running best started over with
+        # the new B (the old one, found with the larger B, has the larger T*)
+        _same_plan(B.alpa_dp_best(h), p_ref)
+        B.alpa_dp_set_B(h, 3)                      # no change of B: the best stays
+        _same_plan(B.alpa_dp_best(h), p_ref)
+        # back to a larger B with no solve since: alpa_dp_best runs the pruned loop itself
+        B.alpa_dp_set_B(h, 50)
+        _, p50 = oracle.solve(w.table, w.N, w.M, 50, w.shapes, allc, True)
+        _same_plan(B.alpa_dp_best(h), p50)
     finally:
         B.alpa_dp_destroy(h)
     # alpa_dp_best on a fresh handle runs the full pruned loop itself
@@ -210,6 +219,96 @@ def test_best_over_several_solves_and_set_B():
     try:
         _, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, allc, True)
         _same_plan(B.alpa_dp_best(h), p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+def test_best_after_a_sweep_only_runs_the_pruned_loop():
+    """A sweep leaves the running best alone, so alpa_dp_best on a handle that has only seen
+    a sweep (or nothing since its table was restricted) still runs Alg. 1's loop itself."""
+    w = W.make_workload(2)
+    allc = oracle.all_candidates(w.table, w.shapes)
+    _, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, allc, True)
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        plans = B.alpa_dp_solve_sweep(h, None, [2, 7])
+        assert plans[0]["num_stages"] > 0
+        assert len(B.alpa_dp_candidates(h)) == len(allc)      # the sweep counts as a solve here
+        _same_plan(B.alpa_dp_best(h), p_ref)
+        B.alpa_dp_solve_sweep(h, None, [5])
+        _same_plan(B.alpa_dp_best(h), p_ref)
+    finally:
+        B.alpa_dp_destroy(h)
+
+
+def test_candidates_from_two_to_the_thirty_on_are_no_filter():
+    """Host candidates may be as large as INT32_MAX - 1; from the device's +infinity sentinel
+    (2^30 - 1) on they filter nothing, and Eq. 4 still adds (B - 1) times the value given."""
+    w = W.make_workload(2)
+    big = np.array([(1 << 30) - 2, (1 << 30) - 1, 1 << 30, 0x3f3f3f3f, 0x3f3f3f40, (1 << 31) - 2,
+                    1000, 1500], dtype=np.int32)
+    for kernel in KERNELS.values():
+        for nc in (1, 2):
+            T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, np.unique(big), False)
+            by_value = dict(zip(np.unique(big).tolist(), T_ref.tolist()))
+            h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+            try:
+                B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_CANDIDATES_PER_WG, nc)
+                T, plan = B.alpa_dp_solve(h, big, flags=kernel)
+                assert T.tolist() == [by_value[int(c)] for c in big]
+                _same_plan(plan, p_ref)
+            finally:
+                B.alpa_dp_destroy(h)
+
+
+def test_create_checks_the_range_of_the_table_on_the_device():
+    import ctypes
+    w = W.make_workload(1)
+    L = B.load()
+    arr = (B.alpa_shape_t * w.S)(*[B.alpa_shape_t(int(n), int(m)) for n, m in w.shapes])
+
+    def create_rc(table):
+        h = ctypes.c_void_p()
+        rc = L.alpa_dp_create(ctypes.byref(h), table.ctypes.data, w.K, w.N, w.M, w.B, arr, w.S)
+        assert (h.value is None) == (rc != 0)
+        if rc == 0:
+            L.alpa_dp_destroy(h)
+        return rc, L.alpa_dp_last_error().decode()
+
+    for pos in ((0, 0, 0, 0), (w.K - 1, w.K - 1, w.K - 1, w.S - 1), (2, 1, 5, 1)):
+        neg = w.table.copy(); neg[pos] = -5
+        rc, msg = create_rc(neg)
+        assert rc == -1 and "negative" in msg
+    # entries below the diagonal are not part of the problem and are not checked
+    low = w.table.copy(); low[0, 3, 1, 0] = -7; low[1, 4, 0, 2] = 2**30
+    assert create_rc(low)[0] == 0
+    big = w.table.copy(); big[big != W.INF_I32] = 2**30 // w.K
+    rc, msg = create_rc(big)
+    assert rc == -2 and "2^30" in msg
+    ok = w.table.copy(); ok[ok != W.INF_I32] = (2**30 - 1) // w.K
+    assert create_rc(ok)[0] == 0
+    allinf = np.full_like(w.table, W.INF_I32)
+    assert create_rc(allinf)[0] == 0
+
+
+def test_tuning_call_rejects_what_it_does_not_know():
+    w = W.make_workload(1)
+    L = B.load()
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        assert L.alpa_dp_set_tuning(None, 1, 1) == -1
+        assert L.alpa_dp_set_tuning(h, 99, 1) == -1
+        assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_CANDIDATES_PER_WG, 3) == -1
+        assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_DISTINCT_BY_SORT, 2) == -1
+        assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_WG_PER_CU, -1) == -1
+        ref = oracle.all_candidates(w.table, w.shapes)
+        T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, ref, False)
+        for key, value in ((B.ALPA_DP_TUNE_WG_PER_CU, 1), (B.ALPA_DP_TUNE_WG_PER_CU, 0),
+                           (B.ALPA_DP_TUNE_DISTINCT_BY_SORT, 1), (B.ALPA_DP_TUNE_DISTINCT_BY_SORT, 0)):
+            B.alpa_dp_set_tuning(h, key, value)
+            T, plan = B.alpa_dp_solve(h, None, 0, 0)
+            assert (T == T_ref).all()
+            _same_plan(plan, p_ref)
     finally:
         B.alpa_dp_destroy(h)
 
@@ -320,12 +419,11 @@ def test_valu_peak_probe_and_readme_example():
 
 @pytest.mark.parametrize("case", [c for c in RANDOM_CASES if c[1] <= 64 and c[2] * c[3] <= 64],
                          ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
-def test_random_tables_two_candidates_per_workgroup(case, monkeypatch):
+def test_random_tables_two_candidates_per_workgroup(case):
     """The register/LDS kernel takes two candidates per workgroup (and packs them into one
-    pass where it can) only for long candidate lists; the tuning variable forces that form
+    pass where it can) only for long candidate lists; the tuning call forces that form
     here, on unstructured tables where most half-blocks need the entry-wise filter, odd
     candidate counts included."""
-    monkeypatch.setenv("ALPA_DP_NC", "2")
     seed, K, N, M = case
     w = W.random_problem(500 + seed, K, N, M, inf_frac=0.25, value_hi=[6, 80, 7000][seed % 3])
     cand_ref = oracle.all_candidates(w.table, w.shapes)
@@ -337,6 +435,7 @@ def test_random_tables_two_candidates_per_workgroup(case, monkeypatch):
         T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, cand_ref, prune, 8)
         h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
         try:
+            B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_CANDIDATES_PER_WG, 2)
             T, plan = B.alpa_dp_solve(h, cand_ref, flags=B.ALPA_DP_PRUNE if prune else 0)
             assert (T == T_ref).all()
             _same_plan(plan, p_ref)
@@ -478,13 +577,12 @@ def test_plans_of_many_stages(case, kernel):
         B.alpa_dp_destroy(h)
 
 
-@pytest.mark.parametrize("nc", ["1", "2"])
+@pytest.mark.parametrize("nc", [1, 2])
 @pytest.mark.parametrize("case", [(1, 128, 8, 8), (2, 96, 4, 8), (3, 72, 2, 8)],
                          ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
-def test_deep_formula_tables(case, nc, monkeypatch):
+def test_deep_formula_tables(case, nc):
     """Structured tables (monotone in the stage span, memory-bound infeasibility) are where
     the early stop of the column loops and the packed two-candidate passes take effect."""
-    monkeypatch.setenv("ALPA_DP_NC", nc)
     seed, K, N, M = case
     w = W.deep_model_problem(seed, K, N, M)
     cand_ref = oracle.quantiles(oracle.all_candidates(w.table, w.shapes), 121)
@@ -493,6 +591,7 @@ def test_deep_formula_tables(case, nc, monkeypatch):
         assert (T_ref < oracle.INF64).any()
         h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
         try:
+            B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_CANDIDATES_PER_WG, nc)
             T, plan = B.alpa_dp_solve(h, cand_ref, flags=B.ALPA_DP_PRUNE if prune else 0)
             assert (T == T_ref).all()
             _same_plan(plan, p_ref)
@@ -505,13 +604,11 @@ def test_deep_formula_tables(case, nc, monkeypatch):
     (90, 6, 2, 2, 50_000_000), (91, 9, 1, 4, (1 << 19) - 1), (92, 9, 1, 4, 1 << 19),
     (93, 40, 4, 4, 3000), (94, 1, 1, 1, 7), (95, 12, 2, 8, 1), (96, 33, 8, 8, 400_000),
 ], ids=lambda c: f"s{c[0]}-K{c[1]}-max{c[4]}")
-def test_candidate_list_by_bitmap_and_by_sort(case, force_sort, monkeypatch):
+def test_candidate_list_by_bitmap_and_by_sort(case, force_sort):
     """The ascending distinct finite table values (the candidates when no list is given) come
     from a presence bitmap when the largest value is below 2^19 and from a radix sort
     otherwise; both against the oracle's list, with zeros, the extreme values present, and the
-    tuning variable that forces the sort."""
-    if force_sort:
-        monkeypatch.setenv("ALPA_DP_SORT", "1")
+    tuning call that forces the sort."""
     seed, K, N, M, hi = case
     w = W.random_problem(seed, K, N, M, inf_frac=0.3, value_hi=hi)
     tab = w.table.copy()
@@ -523,6 +620,8 @@ def test_candidate_list_by_bitmap_and_by_sort(case, force_sort, monkeypatch):
     h = B.alpa_dp_create(tab, K, N, M, w.B, w.shapes)
     try:
         assert B.alpa_dp_count_candidates(h) == len(ref)
+        if force_sort:
+            B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_DISTINCT_BY_SORT, 1)
         T, plan = B.alpa_dp_solve(h, None, 0, 0)
         assert (B.alpa_dp_candidates(h) == ref).all()
         T_ref, p_ref = oracle.solve_parallel(tab, N, M, w.B, w.shapes, ref[:200], False, 8)

@@ -408,3 +408,117 @@ def test_entries_below_the_diagonal_are_ignored():
         T1, p1 = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, c1, False)
         T2, p2 = oracle.solve(t2, w.N, w.M, w.B, w.shapes, c2, False)
         assert (T1 == T2).all() and p1.key() == p2.key()
+
+
+# ---------------------------------------------------------------- index rule of the quantiles
+
+
+def test_quantile_indices_worked_by_hand():
+    """Q evenly spaced quantiles of n sorted values are v[(j * (n - 1)) / (Q - 1)] with the
+    division rounded DOWN, j = 0..Q-1 (all values if n <= Q).  Worked by hand:
+      n = 10, Q = 4: 0*9/3, 1*9/3, 2*9/3, 3*9/3             = 0, 3, 6, 9
+      n = 11, Q = 4: 0, 10/3 = 3.33, 20/3 = 6.67, 30/3       = 0, 3, 6, 10 (nearest: 0, 3, 7, 10)
+      n =  7, Q = 3: 0, 6/2, 12/2                            = 0, 3, 6
+      n =  9, Q = 4: 0, 8/3 = 2.67, 16/3 = 5.33, 8           = 0, 2, 5, 8  (nearest: 0, 3, 5, 8)
+      n =  5, Q = 8: all five."""
+    def idx(n, Q):
+        v = np.arange(100, 100 + 3 * n, 3, dtype=np.int32)     # distinct, ascending
+        q = oracle.quantiles(v, Q)
+        return [int((x - 100) // 3) for x in q]
+    assert idx(10, 4) == [0, 3, 6, 9]
+    assert idx(11, 4) == [0, 3, 6, 10]
+    assert idx(7, 3) == [0, 3, 6]
+    assert idx(9, 4) == [0, 2, 5, 8]
+    assert idx(5, 8) == [0, 1, 2, 3, 4]
+    assert idx(8, 8) == list(range(8))
+    assert idx(2, 2) == [0, 1]
+    assert idx(100, 2) == [0, 99]
+
+
+# ---------------------------------------------------------------- the thread driver's own loop
+
+
+def test_thread_driver_breaks_on_equality_too():
+    """The same hand-computed case as test_prune_breaks_on_equality, through solve_parallel
+    (its break and selection are restated in Python, so they get the pin of their own)."""
+    K, B = 2, 2
+    shapes = np.asarray([[1, 1], [2, 1]], np.int32)
+    table = np.full((K, K, K, 2), INF32, np.int64)
+    table[:, 0, 0, 0] = 2
+    table[:, 1, 1, 0] = 2
+    table[:, 0, 1, 1] = 3
+    table = table.astype(np.int32)
+    cand = np.asarray([2, 3], np.int32)
+    T, p = oracle.solve_parallel(table, 2, 1, B, shapes, cand, False, threads=2)
+    assert list(T) == [6, 6] and p.t_max == 2 and p.num_stages == 2 and p.n_evaluated == 2
+    Tp, pp = oracle.solve_parallel(table, 2, 1, B, shapes, cand, True, threads=2)
+    assert pp.n_evaluated == 1 and Tp[0] == 6 and Tp[1] == INF64 and pp.key() == p.key()
+
+
+def test_thread_driver_equals_sequential_where_the_break_fires_on_equality():
+    """Narrow value ranges make B * t_max == best T* so far a common event; on such tables the
+    thread driver must agree with the sequential C loop in every field, pruning on and off."""
+    n_equal = 0
+    for seed in range(40):
+        rng = np.random.default_rng(1000 + seed)
+        K = int(rng.integers(2, 7))
+        N, M = [(1, 2), (1, 4), (2, 2), (2, 4)][seed % 4]
+        w = W.random_problem(200 + seed, K, N, M, inf_frac=0.15, value_hi=int(rng.integers(3, 7)))
+        Bv = int(rng.integers(1, 5))
+        cand = oracle.all_candidates(w.table, w.shapes)
+        if len(cand) == 0:
+            continue
+        T0, _ = oracle.solve(w.table, w.N, w.M, Bv, w.shapes, cand, False)
+        best = INF64
+        for j, c in enumerate(cand):               # does equality decide a break on this table?
+            if best != INF64 and Bv * int(c) >= best:
+                n_equal += Bv * int(c) == best
+                break
+            best = min(best, int(T0[j]))
+        for prune in (False, True):
+            T1, p1 = oracle.solve(w.table, w.N, w.M, Bv, w.shapes, cand, prune)
+            T2, p2 = oracle.solve_parallel(w.table, w.N, w.M, Bv, w.shapes, cand, prune, threads=3)
+            assert (T1 == T2).all() and p1.key() == p2.key() and p1.n_evaluated == p2.n_evaluated
+    assert n_equal >= 5                             # the case the test is about does occur
+
+
+# ---------------------------------------------------------------- stored results of workloads 3-5
+
+
+@pytest.mark.parametrize("idx", [3, 4, 5])
+def test_stored_results_of_the_large_workloads_satisfy_the_invariants(idx):
+    """Workloads 3-5 are too large for the brute force; what the oracle stored for them
+    (tests/golden/workload_<n>.json, written by make_golden.py from oracle/ alone) must at
+    least satisfy what Sec. 5.2 fixes: stages contiguous and covering, device counts adding up
+    to N * M, every stage <= t_max, sum + (B - 1) t_max = T*, the single-stage plan dominated,
+    and F = T(c) - (B - 1) c non-increasing in the candidate."""
+    import hashlib
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", f"workload_{idx}.json")
+    g = json.load(open(path))
+    w = W.make_workload(idx)
+    assert hashlib.sha256(w.table.tobytes()).hexdigest() == g["table_sha256"]
+    p = oracle.Plan(g["plan"]["T_star"], g["plan"]["t_max"], g["plan"]["num_stages"],
+                    g["plan"]["n_evaluated"], g["plan"]["first_layer"], g["plan"]["shape_idx"])
+    assert p.num_stages >= 1 and len(p.first_layer) == p.num_stages + 1
+    _check_plan_valid(w, p)
+    whole = [q for q in range(w.S) if int(w.sizes[q]) == w.D]
+    t1 = int(w.table[0, 0, w.K - 1, whole[0]])
+    if t1 != INF32:
+        assert p.T_star <= w.B * t1
+    cand = oracle.all_candidates(w.table, w.shapes)
+    assert len(cand) == g["n_distinct"]
+    if w.candidates == "quantiles":
+        cand = oracle.quantiles(cand, w.n_quantiles)
+    assert len(cand) == g["n_candidates"]
+    assert hashlib.sha256(cand.astype("<i4").tobytes()).hexdigest() == g["cand_sha256"]
+    assert p.t_max in cand
+    T97 = np.asarray(g["T_every_97"], dtype=np.int64)
+    c97 = cand[::97].astype(np.int64)
+    assert len(T97) == len(c97)
+    fin = T97 != INF64
+    F97 = T97[fin] - (w.B - 1) * c97[fin]
+    assert (np.diff(F97) <= 0).all()                # F non-increasing in t_max
+    assert not fin[:-1][~fin[1:]].any()             # once feasible, feasible for every larger bound
+    assert (T97[fin] >= p.T_star).all()             # the stored winner is the minimum of the samples
