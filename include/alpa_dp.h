@@ -156,6 +156,9 @@ int alpa_dp_set_B(alpa_dp_t *h, int B);
 #define ALPA_DP_TUNE_DISTINCT_BY_SORT  2  /* 1: distinct table values by the radix sort also where
                                              the presence bitmap applies                        */
 #define ALPA_DP_TUNE_WG_PER_CU         3  /* upper bound on resident workgroups per compute unit */
+#define ALPA_DP_TUNE_WORKGROUPS        4  /* workgroups launched by the register/LDS kernel (own
+                                             choice: as many as are resident at once; more than
+                                             that and each takes fewer candidate groups)        */
 int alpa_dp_set_tuning(alpa_dp_t *h, int key, int value);
 
 /* Number of distinct finite values of the table (entries with i >= k): the length

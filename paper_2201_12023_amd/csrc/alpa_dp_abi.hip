@@ -72,7 +72,7 @@ struct alpa_dp {
     bool have_best = false;         // d_best_plan holds the best of a solve made with the current
                                     // table and B (sweeps do not touch it)
     // tuning (alpa_dp_set_tuning); 0 = the library's own choice
-    int tune_nc = 0, tune_sort = 0, tune_wg_per_cu = 0;
+    int tune_nc = 0, tune_sort = 0, tune_wg_per_cu = 0, tune_grid = 0;
     int fast_per_cu[3] = {0, 0, 0};  // resident workgroups per compute unit, [nc]
 };
 
@@ -489,6 +489,10 @@ extern "C" int alpa_dp_set_tuning(alpa_dp_t *h, int key, int value)
             h->fast_grid_max[nc] = h->n_cu * per_cu;
         }
         return ALPA_DP_OK;
+    case ALPA_DP_TUNE_WORKGROUPS:
+        if (value < 0) return fail(ALPA_DP_EINVAL, "workgroups: >= 0");
+        h->tune_grid = value;
+        return ALPA_DP_OK;
     default:
         return fail(ALPA_DP_EINVAL, "unknown tuning key");
     }
@@ -562,8 +566,9 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
             const bool wide = p.D > 64;            // two windows of device counts, one candidate
             if (wide) nc = 2;
             const int per_wg = wide ? 1 : nc;
-            const int grid =
-                std::max(1, std::min((bound + per_wg - 1) / per_wg, h->fast_grid_max[nc]));
+            const int n_groups = (bound + per_wg - 1) / per_wg;
+            const int grid = std::max(
+                1, std::min(n_groups, h->tune_grid ? h->tune_grid : h->fast_grid_max[nc]));
             FastArgs fa{p, h->d_recs, h->d_sizes, h->d_cand, &h->d_state->n_cand,
                         &h->d_state->ticket, &h->d_state->wave_relax, h->d_chunkmin, prune,
                         /*descending=*/prune ? 0 : 1, h->d_Fmin, h->d_Sbest, h->cand_cap, nullptr, nullptr, h->d_gmin};
