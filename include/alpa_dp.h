@@ -284,6 +284,35 @@ int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
                         int32_t *out_first_op, float *out_ms);
 
 /*
+ * alpa_cluster_layers for callers that cannot allocate device memory or wait: code recorded into
+ * a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same computation and
+ * results; inputs and outputs are DEVICE pointers owned by the caller, the call only queues
+ * kernels on `hip_stream` (a hipStream_t, NULL = the null stream) and returns; it calls no
+ * hipMalloc / hipFree, copies nothing and does not synchronise.  The work memory is a fixed
+ * array in the library's device image (about 3.2 MB per device, held until the process ends),
+ * which limits K and L to ALPA_CLUSTER_STATIC_MAX_OPS.
+ *
+ *   d_flop, d_edge_src, d_edge_dst, d_edge_bytes   as for alpa_cluster_layers, device memory.
+ *   d_out           int64 [3]: G(K, L) (ALPA_DP_INF_I64 if none), sum of squared per-layer
+ *                   FLOP, and the status of the argument checks that alpa_cluster_layers makes
+ *                   on the host and this call makes on the device: 0, ALPA_DP_EINVAL (negative
+ *                   figure, bad edge) or ALPA_DP_EOVERFLOW; if not 0 the other outputs are
+ *                   those of "no clustering" (INF, 0, -1 ...).  A bad edge is never written.
+ *   d_out_first_op  int32 [L + 1].
+ * All calls on one device share the one work array: calls that may run at the same time on a
+ * device (different streams, different threads) race; serialise them.  Results are valid once
+ * the stream has run the work; the input arrays must stay unchanged until then.
+ *
+ * Errors (returned at once, nothing queued): EINVAL (null pointer, K or L < 1 or above
+ * ALPA_CLUSTER_STATIC_MAX_OPS, num_edges < 0, delta_ppm out of range), EHIP.
+ */
+#define ALPA_CLUSTER_STATIC_MAX_OPS 512
+int alpa_cluster_layers_static(const int32_t *d_flop, int K, const int32_t *d_edge_src,
+                               const int32_t *d_edge_dst, const int64_t *d_edge_bytes,
+                               int num_edges, int L, int delta_ppm, int64_t *d_out,
+                               int32_t *d_out_first_op, void *hip_stream);
+
+/*
  * Physical placement of the submeshes a plan chose (Sec. 5.2: devices go to larger submeshes
  * first, then to smaller ones, and neighbouring stages of one shape are put next to each other;
  * Appendix A shows the shapes always cover the mesh, and the construction follows its proof).

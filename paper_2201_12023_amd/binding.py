@@ -19,6 +19,7 @@ MAX_K = 256
 MAX_SWEEP = 256
 MAX_OPTIONS = 32
 CLUSTER_MAX_OPS = 4096
+CLUSTER_STATIC_MAX_OPS = 512
 INF_I32 = 2**31 - 1
 INF_I64 = 2**63 - 1
 ALPA_DP_PRUNE = 1
@@ -34,7 +35,7 @@ SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table"
            "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
            "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
-           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_place_submeshes", "alpa_dp_measure_valu_peak"]
+           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_cluster_layers_static", "alpa_place_submeshes", "alpa_dp_measure_valu_peak"]
 
 
 class alpa_shape_t(ctypes.Structure):
@@ -100,6 +101,8 @@ def load():
     L.alpa_cluster_layers.argtypes = [vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, i64p, i64p, vp,
                                       ctypes.POINTER(ctypes.c_float)]
+    L.alpa_cluster_layers_static.argtypes = [vp, ctypes.c_int, vp, vp, vp, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_int, vp, vp, vp]
     L.alpa_place_submeshes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(alpa_shape_t),
                                        ctypes.c_int, vp, vp]
     L.alpa_dp_measure_valu_peak.argtypes = [ctypes.POINTER(ctypes.c_double)]
@@ -282,6 +285,21 @@ def alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm):
     feasible = comm.value != INF_I64
     return {"comm": int(comm.value), "sumsq": int(sumsq.value),
             "first_op": [int(x) for x in first] if feasible else [], "ms": float(ms.value)}
+
+
+def alpa_cluster_layers_static(d_flop, d_edge_src, d_edge_dst, d_edge_bytes, L, delta_ppm, d_out,
+                               d_out_first_op, stream=None):
+    """Allocation-free, asynchronous variant: torch CUDA tensors in (int32 / int32 / int32 /
+    int64) and out (d_out int64 [3], d_out_first_op int32 [L + 1]); stream: a torch.cuda.Stream,
+    a raw handle or None (null stream)."""
+    def ptr(t):
+        return None if t is None or t.numel() == 0 else ctypes.c_void_p(int(t.data_ptr()))
+    raw = 0 if stream is None else int(getattr(stream, "cuda_stream", stream))
+    E = 0 if d_edge_src is None else int(d_edge_src.numel())
+    _check(load().alpa_cluster_layers_static(ptr(d_flop), int(d_flop.numel()), ptr(d_edge_src),
+                                             ptr(d_edge_dst), ptr(d_edge_bytes), E, int(L),
+                                             int(delta_ppm), ptr(d_out), ptr(d_out_first_op),
+                                             ctypes.c_void_p(raw)))
 
 
 def alpa_place_submeshes(N, M, stage_shapes):

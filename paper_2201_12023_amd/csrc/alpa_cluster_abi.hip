@@ -101,3 +101,62 @@ extern "C" int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *ed
     if (out_ms) HIPCHK(hipEventElapsedTime(out_ms, ev0, ev1));
     return ALPA_DP_OK;
 }
+
+// ---------------------------------------------------------------- no allocation on the call
+
+// Work memory of alpa_cluster_layers_static: what alpa_cluster_layers allocates per call, at
+// the sizes of ALPA_CLUSTER_STATIC_MAX_OPS operators and layers, in int64 units:
+// Ct [K*K], chunk [ceil(K/64)*K], pf [K+1], GV [4*(K+1)], ctl [8], arg [L*(K+1)] int32.
+namespace {
+constexpr size_t SMAX = ALPA_CLUSTER_STATIC_MAX_OPS;
+constexpr size_t SCRATCH_I64 = SMAX * SMAX + ((SMAX + 63) / 64) * SMAX + (SMAX + 1) +
+                               4 * (SMAX + 1) + 8 + (SMAX * (SMAX + 1) + 1) / 2;
+}
+// Every device the library runs on holds its own copy of this array until the process ends.  In
+// host code the name is only a handle for hipGetSymbolAddress; kernels get the address below.
+static __device__ __align__(256) int64_t scratch[SCRATCH_I64];
+
+namespace {
+constexpr int MAX_DEV = 64;
+int64_t *g_scratch_of_device[MAX_DEV];      // device address of `scratch`, per device
+bool g_scratch_known[MAX_DEV];
+}
+
+extern "C" int alpa_cluster_layers_static(const int32_t *d_flop, int K, const int32_t *d_edge_src,
+                                          const int32_t *d_edge_dst, const int64_t *d_edge_bytes,
+                                          int num_edges, int L, int delta_ppm, int64_t *d_out,
+                                          int32_t *d_out_first_op, void *hip_stream)
+{
+    if (!d_flop || !d_out || !d_out_first_op) return fail(ALPA_DP_EINVAL, "null argument");
+    if (K < 1 || L < 1) return fail(ALPA_DP_EINVAL, "K or L < 1");
+    if (K > ALPA_CLUSTER_STATIC_MAX_OPS || L > ALPA_CLUSTER_STATIC_MAX_OPS)
+        return fail(ALPA_DP_EINVAL, "K or L exceeds ALPA_CLUSTER_STATIC_MAX_OPS (the fixed work "
+                                    "memory of this entry point); use alpa_cluster_layers");
+    if (num_edges < 0 || (num_edges > 0 && (!d_edge_src || !d_edge_dst || !d_edge_bytes)))
+        return fail(ALPA_DP_EINVAL, "edge list is null or num_edges < 0");
+    if (delta_ppm < 0 || delta_ppm > 1000000000) return fail(ALPA_DP_EINVAL, "delta_ppm out of range");
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEV) return fail(ALPA_DP_EINVAL, "device index out of range");
+    if (!g_scratch_known[dev]) {                   // set-up, once per device, that device current
+        int64_t *ptr = nullptr;
+        HIPCHK(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(ALPA_DP_EHIP, "hipGetSymbolAddress gave a null address");
+        g_scratch_of_device[dev] = ptr;
+        g_scratch_known[dev] = true;
+    }
+    int64_t *base = g_scratch_of_device[dev];
+    const size_t Ks = (size_t)K;
+    int64_t *Ct = base;
+    int64_t *chunk = Ct + Ks * Ks;
+    int64_t *pf = chunk + cluster_chunk_rows(K) * Ks;
+    int64_t *GV = pf + (Ks + 1);
+    int64_t *ctl = GV + 4 * (Ks + 1);
+    int32_t *arg = (int32_t *)(ctl + 8);
+    // Everything the kernels read from the work memory they have written in this call (Ct is
+    // cleared by a fill kernel, not a memset, so that the call can be recorded into a graph).
+    HIPCHK(launch_cluster((hipStream_t)hip_stream, d_flop, d_edge_src, d_edge_dst, d_edge_bytes,
+                          num_edges, K, L, /*cap=*/0, Ct, chunk, pf, GV, arg, d_out, d_out_first_op,
+                          ctl, delta_ppm));
+    return ALPA_DP_OK;
+}

@@ -205,11 +205,15 @@ hipError_t launch_init_state(hipStream_t st, SolveState *state, int64_t *chunk_m
 hipError_t launch_init_best_plan(hipStream_t st, void *best_plan);
 
 // operator clustering (Eq. 6); buffers: Ct [K*K], chunk [cluster_chunk_rows(K)*K], pf [K+1],
-// GV [4*(K+1)] (int64), arg [L*(K+1)], out [2] (G, V), first_op [L+1]
+// GV [4*(K+1)] (int64), arg [L*(K+1)], out [2] (G, V), first_op [L+1].  ctl == nullptr: the
+// caller has checked the inputs and passes the FLOP bound `cap`.  ctl != nullptr ([2] int64):
+// the inputs are checked and the bound is computed from delta_ppm on the device, out is [3]
+// (G, V, status) and `cap` is ignored.
 hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *src,
                           const int32_t *dst, const int64_t *nbytes, int E, int K, int L,
                           int64_t cap, int64_t *Ct, int64_t *chunk, int64_t *pf, int64_t *GV,
-                          int32_t *arg, int64_t *out, int32_t *first_op);
+                          int32_t *arg, int64_t *out, int32_t *first_op, int64_t *ctl = nullptr,
+                          int delta_ppm = 0);
 size_t cluster_chunk_rows(int K);
 
 }  // namespace alpa

@@ -54,9 +54,73 @@ __global__ void edges_to_matrix_kernel(const int32_t *__restrict__ src, const in
                                        const int64_t *__restrict__ nbytes, int E, int K,
                                        int64_t *__restrict__ Wt)
 {
-    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < E; e += gridDim.x * blockDim.x)
-        atomicAdd((unsigned long long *)&Wt[(size_t)dst[e] * K + src[e]],
-                  (unsigned long long)nbytes[e]);
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < E; e += gridDim.x * blockDim.x) {
+        const int u = src[e], v = dst[e];
+        // callers with host arrays have checked this already; with device arrays the check
+        // kernel reports such an edge, and here it must not be written
+        if (u < 0 || v >= K || u >= v) continue;
+        atomicAdd((unsigned long long *)&Wt[(size_t)v * K + u], (unsigned long long)nbytes[e]);
+    }
+}
+
+// Argument checks for device-resident inputs (what alpa_cluster_layers does on the host):
+// ctl[0] = 0, ALPA_DP_EINVAL (-1: negative figure, bad edge) or ALPA_DP_EOVERFLOW (-2: total FLOP
+// >= 2^31, total * L >= 2^42, edge sizes adding up to >= 2^62); ctl[1] = the FLOP bound per
+// layer, floor((10^6 + delta_ppm) * total / (L * 10^6)).  One block.
+__global__ __launch_bounds__(1024) void cluster_check_kernel(
+    const int32_t *__restrict__ flop, int K, const int32_t *__restrict__ src,
+    const int32_t *__restrict__ dst, const int64_t *__restrict__ nbytes, int E, int L,
+    int delta_ppm, int64_t *__restrict__ ctl)
+{
+    __shared__ unsigned long long sh_flop, sh_bytes;
+    __shared__ int sh_bad, sh_over;
+    const int t = threadIdx.x;
+    if (t == 0) { sh_flop = 0; sh_bytes = 0; sh_bad = 0; sh_over = 0; }
+    __syncthreads();
+    constexpr unsigned long long LIM = 1ull << 62;
+    unsigned long long f = 0, b = 0;
+    int bad = 0, over = 0;
+    for (int k = t; k < K; k += 1024) {
+        const int32_t v = flop[k];
+        if (v < 0) bad = 1; else f += (unsigned long long)v;        // < 2^31 * 4 per thread
+    }
+    for (int e = t; e < E; e += 1024) {
+        const int u = src[e], v = dst[e];
+        const int64_t n = nbytes[e];
+        if (u < 0 || v >= K || u >= v || n < 0) { bad = 1; continue; }
+        if ((unsigned long long)n >= LIM) over = 1;
+        b = min(LIM, b + min(LIM, (unsigned long long)n));         // saturating: stays <= 2^62
+    }
+    atomicAdd(&sh_flop, f);
+    if (bad) atomicOr(&sh_bad, 1);
+    if (over) atomicOr(&sh_over, 1);
+    __syncthreads();
+    // the byte total, saturating, one thread after the other (1024 partial sums <= 2^62 each
+    // would wrap an unsigned 64-bit add)
+    for (int turn = 0; turn < 1024; turn += WAVE) {
+        if (t >= turn && t < turn + WAVE) {
+            unsigned long long x = b;
+            for (int off = 32; off >= 1; off >>= 1) {
+                const unsigned long long o =
+                    (unsigned long long)i64_from(__shfl_xor(lo32((int64_t)x), off, 64),
+                                                 __shfl_xor(hi32((int64_t)x), off, 64));
+                x = min(LIM, x + o);
+            }
+            if ((t & (WAVE - 1)) == 0) sh_bytes = min(LIM, sh_bytes + x);
+        }
+        __syncthreads();
+    }
+    if (t == 0) {
+        const unsigned long long total = sh_flop;
+        int64_t status = 0;
+        if (sh_bad) status = -1;
+        else if (total >= (1ull << 31) || total * (unsigned long long)L >= (1ull << 42) ||
+                 sh_over || sh_bytes >= LIM) status = -2;
+        ctl[0] = status;
+        ctl[1] = status ? 0
+                        : (int64_t)(((1000000ull + (unsigned long long)delta_ppm) * total) /
+                                    ((unsigned long long)L * 1000000ull));
+    }
 }
 
 // row v: A[v][i] = sum over u < i of Wt[v][u], i = 0..K-1, in place (one block per row)
@@ -154,9 +218,11 @@ __device__ __forceinline__ Lex lex_shfl_xor(const Lex &a, int m)
 // One layer count r: Gn[n], Vn[n], arg[n] for n = 1..K from Gp, Vp (r - 1).  One wave per n.
 __global__ __launch_bounds__(256) void cluster_layer_kernel(
     const int64_t *__restrict__ Ct, const int64_t *__restrict__ pf, int K, int64_t cap,
-    const int64_t *__restrict__ Gp, const int64_t *__restrict__ Vp, int64_t *__restrict__ Gn,
-    int64_t *__restrict__ Vn, int32_t *__restrict__ arg)
+    const int64_t *__restrict__ ctl, const int64_t *__restrict__ Gp,
+    const int64_t *__restrict__ Vp, int64_t *__restrict__ Gn, int64_t *__restrict__ Vn,
+    int32_t *__restrict__ arg)
 {
+    if (ctl) cap = ctl[1];                          // bound computed on the device (cluster_check_kernel)
     const int lane = threadIdx.x & (WAVE - 1);
     const int n = blockIdx.x * 4 + (threadIdx.x >> 6) + 1;          // prefix length, 1-based
     if (n > K) return;                                              // whole wave
@@ -190,13 +256,17 @@ __global__ __launch_bounds__(256) void cluster_layer_kernel(
     if (lane == 0 && n == 1) { Gn[0] = INF_I64; Vn[0] = 0; arg[0] = 0; }   // G(0, r > 0)
 }
 
-// out[0] = G(K, L), out[1] = V(K, L); first_op[0..L] by walking arg back (one thread)
+// out[0] = G(K, L), out[1] = V(K, L); first_op[0..L] by walking arg back (one thread).  With
+// ctl (device-resident inputs) also out[2] = ctl[0], the status of the argument checks, and
+// "no clustering" is reported if that is not 0.
 __global__ void cluster_walk_kernel(const int64_t *__restrict__ G, const int64_t *__restrict__ V,
                                     const int32_t *__restrict__ arg, int K, int L,
-                                    int64_t *__restrict__ out, int32_t *__restrict__ first_op)
+                                    const int64_t *__restrict__ ctl, int64_t *__restrict__ out,
+                                    int32_t *__restrict__ first_op)
 {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    const int64_t g = G[K];
+    if (ctl) out[2] = ctl[0];
+    const int64_t g = (ctl && ctl[0] != 0) ? INF_I64 : G[K];
     out[0] = g;
     out[1] = g == INF_I64 ? 0 : V[K];
     if (g == INF_I64) {
@@ -215,8 +285,12 @@ __global__ void cluster_walk_kernel(const int64_t *__restrict__ G, const int64_t
 hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *src,
                           const int32_t *dst, const int64_t *nbytes, int E, int K, int L,
                           int64_t cap, int64_t *Ct, int64_t *chunk, int64_t *pf, int64_t *GV,
-                          int32_t *arg, int64_t *out, int32_t *first_op)
+                          int32_t *arg, int64_t *out, int32_t *first_op, int64_t *ctl,
+                          int delta_ppm)
 {
+    if (ctl)
+        hipLaunchKernelGGL(cluster_check_kernel, dim3(1), dim3(1024), 0, st, flop, K, src, dst,
+                           nbytes, E, L, delta_ppm, ctl);
     hipLaunchKernelGGL(flop_prefix_kernel, dim3(1), dim3(1024), 0, st, flop, K, pf);
     const long long kk = (long long)K * K;
     hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)std::min<long long>((kk + 255) / 256, 4096)),
@@ -238,10 +312,11 @@ hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *sr
     for (int r = 1; r <= L; ++r) {
         const int p = (r - 1) & 1, c = r & 1;
         hipLaunchKernelGGL(cluster_layer_kernel, dim3((K + 3) / 4), dim3(256), 0, st, Ct, pf, K, cap,
-                           G[p], V[p], G[c], V[c], arg + (size_t)(r - 1) * (K + 1));
+                           (const int64_t *)ctl, G[p], V[p], G[c], V[c],
+                           arg + (size_t)(r - 1) * (K + 1));
     }
     hipLaunchKernelGGL(cluster_walk_kernel, dim3(1), dim3(WAVE), 0, st, G[L & 1], V[L & 1], arg, K, L,
-                       out, first_op);
+                       (const int64_t *)ctl, out, first_op);
     return hipGetLastError();
 }
 
