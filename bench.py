@@ -39,8 +39,9 @@ def stored_counter_figures(workload):
     tr = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
     fi = re.search(r"^valu_issued_fraction:\s*([0-9.eE+-]+)", text, re.M)
     co = re.search(r"^measured_at_commit:\s*(\w+)", text, re.M)
+    tc = re.search(r"^traffic_measured_at_commit:\s*(\w+)", text, re.M)
     return (float(tr.group(1)) if tr else None, float(fi.group(1)) if fi else None,
-            co.group(1) if co else None)
+            (tc or co).group(1) if (tc or co) else None)
 
 
 def main():
