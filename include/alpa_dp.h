@@ -152,7 +152,7 @@ int alpa_dp_set_B(alpa_dp_t *h, int B);
  * library's own choice.  Errors: EINVAL (null handle, unknown key, value out of range).
  */
 #define ALPA_DP_TUNE_CANDIDATES_PER_WG 1  /* 1 or 2 t_max candidates per workgroup of the
-                                             register/LDS kernel (own choice: 2 for long lists)  */
+                                             register/LDS kernel (own choice: 1)                 */
 #define ALPA_DP_TUNE_DISTINCT_BY_SORT  2  /* 1: distinct table values by the radix sort also where
                                              the presence bitmap applies                        */
 #define ALPA_DP_TUNE_WG_PER_CU         3  /* upper bound on resident workgroups per compute unit */

@@ -559,9 +559,11 @@ static int solve_dev_impl(alpa_dp *h, const int32_t *d_tmax, int n_tmax, unsigne
     if (bound > 0) {
         const bool fast = h->fast_ok && !(flags & ALPA_DP_GENERIC);
         if (fast) {
-            // two candidates per workgroup share every scalar load; worth it once there are
-            // enough candidates to fill the device twice over that way
-            int nc = (bound >= 4 * h->fast_grid_max[2]) ? 2 : 1;
+            // One candidate per workgroup: seven waves per SIMD and two columns folded into one
+            // three-operand minimum, which is faster than two candidates sharing their scalar
+            // loads and lanes at four waves per SIMD (workload 4: 4.40 against 4.66 ms); the
+            // two-candidate form stays available through the tuning call.
+            int nc = 1;
             if (h->tune_nc) nc = h->tune_nc;
             const bool wide = p.D > 64;            // two windows of device counts, one candidate
             if (wide) nc = 2;

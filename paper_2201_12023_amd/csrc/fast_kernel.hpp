@@ -117,6 +117,48 @@ __device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)
     }
 }
 
+// Two columns of one half-block in one go (single candidate): acc = min3(acc, tX + GX, tY + GY),
+// three vector instructions for two cell-updates per row instead of four.  Worth it where the
+// kernel is bound by vector issue, which the one-candidate instances are (seven waves per SIMD).
+__device__ __forceinline__ void relax_update2(int32_t *acc, int off, const int32_t (&tX)[8], int32_t GX,
+                                              const int32_t (&tY)[8], int32_t GY)
+{
+#pragma unroll
+    for (int h = 0; h < 8; h += 4) {               // four rows at a time: eight sums in flight
+        int32_t sx[4], sy[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { sx[u] = tX[h + u] + GX; sy[u] = tY[h + u] + GY; }
+        asm volatile("" : "+v"(sx[0]), "+v"(sx[1]), "+v"(sx[2]), "+v"(sx[3]), "+v"(sy[0]),
+                          "+v"(sy[1]), "+v"(sy[2]), "+v"(sy[3]));
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[off + h + u] = min(acc[off + h + u], min(sx[u], sy[u]));
+    }
+}
+
+template <bool COUNT>
+__device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnX,
+                                         int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mnY,
+                                         int32_t mxY, int32_t GY, int32_t c, unsigned &n_blocks)
+{
+    // One path: skipped if neither half-column has an entry for the candidate, else both are
+    // filtered where needed and folded.  A half-column with nothing for the candidate has its
+    // maximum above it too, so the filter turns it into all-infinite entries, which the
+    // minimum ignores: no separate code for "only one of the two", whose extra exits cost the
+    // common path several taken branches.
+    if (mnX <= c || mnY <= c) {
+        if (mxX > c) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) tX[u] = (tX[u] <= c) ? tX[u] : DEV_INF;
+        }
+        if (mxY > c) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) tY[u] = (tY[u] <= c) ? tY[u] : DEV_INF;
+        }
+        if (COUNT) n_blocks += (mnX <= c ? 1 : 0) + (mnY <= c ? 1 : 0);
+        relax_update2(acc, off, tX, GX, tY, GY);
+    }
+}
+
 // Two candidates in one pass.  Where every device count a shape can still serve at this layer
 // lies in one window of 32 (d - 1 in [base, base + 32)), lanes 0..31 work for candidate 0 and
 // lanes 32..63 for candidate 1, both on that window: the scalar t_intra values are the same
@@ -173,7 +215,8 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // accumulator sets and the two LDS regions that otherwise belong to two candidates hold the
 // device counts 1..64 and 65..128 of the one candidate ("windows" 0 and 1).
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
-__global__ __launch_bounds__(WAVE * NWK * WI) __attribute__((amdgpu_waves_per_eu(4)))
+__global__ __launch_bounds__(WAVE * NWK * WI)
+__attribute__((amdgpu_waves_per_eu((NC == 1 && WI == 1 && !DUMP && !WIDE) ? 7 : 4)))
 void recurrence_fast_kernel(
     Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
@@ -212,6 +255,8 @@ void recurrence_fast_kernel(
     // candidate packing (two candidates, one pass): lane l works for candidate l / 32 on
     // device count d - 1 = pk_base + l % 32
     constexpr bool PACK = NC == 2 && WI == 1 && !DUMP && !WIDE;
+    // one candidate per workgroup: two columns folded into one three-operand minimum per row
+    constexpr bool FOLD = NC == 1 && WI == 1 && !DUMP && !WIDE;
     const int pk_base = max(0, D - 32);
     const int pk_dl = pk_base + (lane & 31);
     const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
@@ -418,10 +463,17 @@ void recurrence_fast_kernel(
                             fence_loads();
                         };
                         auto compute2 = [&](Batch &b) {
-                            operands(b.fX);
-                            relax(off, b.X, mnf(b.X));
-                            operands(b.fY);
-                            relax(off, b.Y, mnf(b.Y));
+                            if constexpr (FOLD) {
+                                const int32_t GX = live ? b.fX[0] : DEV_INF;
+                                const int32_t GY = live ? b.fY[0] : DEV_INF;
+                                relax8x2<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, GX, b.Y.t,
+                                                mnf(b.Y), b.Y.mx, GY, c[0], n_blocks);
+                            } else {
+                                operands(b.fX);
+                                relax(off, b.X, mnf(b.X));
+                                operands(b.fY);
+                                relax(off, b.Y, mnf(b.Y));
+                            }
                         };
                         auto settle2 = [&](const Batch &b) {
                             settle(b.X, b.fX[0]);
@@ -457,6 +509,15 @@ void recurrence_fast_kernel(
                     };
                     // columns of each phase; endA / endB bound where the half-blocks still
                     // have something for the largest candidate
+                    if constexpr (FOLD) {
+                        // every column pair of a half-block folds, so the half-blocks go one
+                        // after the other (the operand row of a column is read once for each)
+                        const int cB0 = max(i0, rowB);
+                        single(0, pA, row_ptr(i0), max(0, min(i_hi + 1, endA) - i0), mnA);
+                        single(8, pB + (size_t)(cB0 - i0) * STEP, row_ptr(cB0),
+                               max(0, min(i_hi + 1, endB) - cB0), mnB);
+                        return;
+                    }
                     const int n1 = max(0, min(rowB - i0, ncol));       // reach half-block A only
                     const int cAB = i0 + n1;                           // first column reaching B
                     const int stopAB = endA > endB ? endA : min(endA, endB);
