@@ -350,7 +350,12 @@ void recurrence_fast_kernel(
 #pragma unroll
         for (int e = 0; e < NC; ++e) { best[e] = DEV_INF; sbest[e] = 0; }
         unsigned n_blocks = 0;
-        for (int s = 1; s <= s_top; ++s) {
+        // One layer of Eq. 3.  The first layer has a form of its own (the only finite operand is
+        // F(0, K+1, 0) = 0) and is a separate instance of this body, in front of the loop over
+        // the others: inside one loop the two forms meet at every shape, and the accumulators
+        // are copied from one register set to another and back there.
+        auto layer = [&](const int s, auto FIRST_T) {
+            constexpr bool FIRST = decltype(FIRST_T)::value;
             const bool needA = !DUMP || rowA + 7 >= s_top - s;
             const bool needB = !DUMP || rowB + 7 >= s_top - s;
             auto mnA = [&](const HalfColumn &h) { return needA ? h.mn : DEV_INF; };   // "no entry
@@ -364,7 +369,7 @@ void recurrence_fast_kernel(
 #pragma unroll
             for (int u = 0; u < 16; ++u) accP[u] = DEV_INF;
             int32_t c2[2] = {c[0], c[NC - 1]};
-            const int i_lo = (s == 1) ? K - 1 : 0;     // 0-based last layer
+            const int i_lo = FIRST ? K - 1 : 0;        // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
             const int i0 = max(i_lo, rowA);            // columns that reach half-block A
             if (WI > 1) {
@@ -381,7 +386,7 @@ void recurrence_fast_kernel(
                 if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
                 if (i0 > i_hi) continue;
                 // packed when every device count the shape can still serve is in the window
-                if ((PACK && s > 1 && a + s - 2 >= pk_base) != PASS_P) continue;
+                if ((PACK && !FIRST && a + s - 2 >= pk_base) != PASS_P) continue;
                 // first column group without anything for the largest candidate, per half-block
                 int endA = K, endB = K;
                 if (q < END_SHAPES) {
@@ -390,7 +395,7 @@ void recurrence_fast_kernel(
                     endA = needA ? GW * (bits & 15) : 0;
                     endB = needB ? GW * ((bits >> 4) & 15) : 0;
                 }
-                if (s > 1 && endA <= i0 && endB <= rowB) continue;   // nothing alive in reach
+                if (!FIRST && endA <= i0 && endB <= rowB) continue;  // nothing alive in reach
                 if (PASS_P) packed_any = true;
                 constexpr int STEP = REC;
                 const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
@@ -398,7 +403,7 @@ void recurrence_fast_kernel(
                 const int ncol = i_hi - i0 + 1;                // columns of this wave
                 HalfColumn hA, hB;
                 int32_t G[NC];
-                if (s == 1) {
+                if constexpr (FIRST) {
                     // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
 #pragma unroll
                     for (int e = 0; e < NC; ++e)
@@ -410,8 +415,7 @@ void recurrence_fast_kernel(
                         relax8<NC, COUNT>(acc, 0, hA.t, mnA(hA), hA.mx, G, c, n_blocks);
                         if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, mnB(hB), hB.mx, G, c, n_blocks);
                     }
-                    continue;
-                }
+                } else {
                 auto columns = [&](auto PK) {
                     // Pipeline, one batch ahead.  A batch is two half-columns (slots X and Y) with
                     // their LDS rows; while one batch is computed the loads of the next are in
@@ -464,10 +468,9 @@ void recurrence_fast_kernel(
                         };
                         auto compute2 = [&](Batch &b) {
                             if constexpr (FOLD) {
-                                const int32_t GX = live ? b.fX[0] : DEV_INF;
-                                const int32_t GY = live ? b.fY[0] : DEV_INF;
-                                relax8x2<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, GX, b.Y.t,
-                                                mnf(b.Y), b.Y.mx, GY, c[0], n_blocks);
+                                // (runs with only the lanes that have an operand switched on)
+                                relax8x2<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
+                                                mnf(b.Y), b.Y.mx, b.fY[0], c[0], n_blocks);
                             } else {
                                 operands(b.fX);
                                 relax(off, b.X, mnf(b.X));
@@ -512,10 +515,16 @@ void recurrence_fast_kernel(
                     if constexpr (FOLD) {
                         // every column pair of a half-block folds, so the half-blocks go one
                         // after the other (the operand row of a column is read once for each)
+                        // Lanes below the shape's size have no operand (d - a_q < 1) and nothing
+                        // to update: they sit the pass out, which saves the select of the
+                        // operand per column.  (Not a branch on the lane id alone: the set
+                        // changes with the shape, so the loops around are not split on it.)
                         const int cB0 = max(i0, rowB);
-                        single(0, pA, row_ptr(i0), max(0, min(i_hi + 1, endA) - i0), mnA);
-                        single(8, pB + (size_t)(cB0 - i0) * STEP, row_ptr(cB0),
-                               max(0, min(i_hi + 1, endB) - cB0), mnB);
+                        if (live) {
+                            single(0, pA, row_ptr(i0), max(0, min(i_hi + 1, endA) - i0), mnA);
+                            single(8, pB + (size_t)(cB0 - i0) * STEP, row_ptr(cB0),
+                                   max(0, min(i_hi + 1, endB) - cB0), mnB);
+                        }
                         return;
                     }
                     const int n1 = max(0, min(rowB - i0, ncol));       // reach half-block A only
@@ -568,6 +577,7 @@ void recurrence_fast_kernel(
                     single(8, pB + (size_t)(cB - i0) * STEP, row_ptr(cB), nB, mnB);
                 };
                 columns(PASS_PACKED);
+                }
             }
             };
             shapes_pass(std::false_type{});
@@ -632,7 +642,9 @@ void recurrence_fast_kernel(
                     }
                 }
             }
-        }
+        };
+        if (s_top >= 1) layer(1, std::true_type{});
+        for (int s = 2; s <= s_top; ++s) layer(s, std::false_type{});
         // lane D-1 (of window (D-1)/64) holds F(s, first layer, all devices); wave 0 owns the
         // results; a repeated last candidate goes to the spare slot
 #pragma unroll
@@ -655,7 +667,8 @@ void recurrence_fast_kernel(
         if (COUNT) n_blocks_total += n_blocks;
         __syncthreads();                               // LDS is reused by the next group
     }
-    if (COUNT) atomicAdd(wave_relax, lane == 0 ? n_blocks_total * 8ull : 0ull);
+    // (the last lane: it takes part in every pass, also where the low lanes sit one out)
+    if (COUNT) atomicAdd(wave_relax, lane == WAVE - 1 ? n_blocks_total * 8ull : 0ull);
 }
 
 // shape-axis wave groups of the single-candidate (plan) run: as many as 1024 threads allow
