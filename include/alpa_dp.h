@@ -156,6 +156,10 @@ int alpa_dp_set_B(alpa_dp_t *h, int B);
 #define ALPA_DP_TUNE_DISTINCT_BY_SORT  2  /* 1: distinct table values by the radix sort also where
                                              the presence bitmap applies                        */
 #define ALPA_DP_TUNE_WG_PER_CU         3  /* upper bound on resident workgroups per compute unit */
+#define ALPA_DP_TUNE_LANE_GROUPS        5  /* meshes of up to 32 devices: 1 = do not cut the wave
+                                             into lane groups with a candidate each; 2, 4, .. 64
+                                             = that many groups (at most 64 / devices rounded up
+                                             to a power of two)                                 */
 #define ALPA_DP_TUNE_WORKGROUPS        4  /* workgroups launched by the register/LDS kernel (own
                                              choice: as many as are resident at once; more than
                                              that and each takes fewer candidate groups)        */

@@ -29,6 +29,7 @@ ALPA_DP_TUNE_CANDIDATES_PER_WG = 1
 ALPA_DP_TUNE_DISTINCT_BY_SORT = 2
 ALPA_DP_TUNE_WG_PER_CU = 3
 ALPA_DP_TUNE_WORKGROUPS = 4
+ALPA_DP_TUNE_LANE_GROUPS = 5
 
 SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table",
            "alpa_dp_restrict_equal_layers", "alpa_dp_set_stream", "alpa_dp_set_B", "alpa_dp_set_tuning", "alpa_dp_count_candidates",

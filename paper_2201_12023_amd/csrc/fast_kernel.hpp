@@ -159,6 +159,56 @@ __device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8]
     }
 }
 
+// Small meshes (GROUPED): the wave's lanes are cut into groups of DP = 2^ceil(log2 D) <= 32
+// lanes, group g works for candidate j0 + g on device counts 1..DP, and all groups share every
+// scalar t_intra.  The scalar side filters against the largest candidate of the wave (c_hi, as
+// for a single candidate); entries between the smallest (c_lo) and c_hi pass for some groups
+// only and are then filtered lane by lane against the lane's own candidate.
+__device__ __forceinline__ void relax_update_lanes(int32_t *acc, int off, const int32_t (&t)[8],
+                                                   int32_t G, int32_t c_lane)
+{
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int32_t sum = (t[u] <= c_lane) ? t[u] + G : DEV_INF;
+        acc[off + u] = min(acc[off + u], sum);
+    }
+}
+
+template <bool COUNT>
+__device__ __forceinline__ void relax8g(int32_t *acc, int off, int32_t (&t)[8], int32_t mn, int32_t mx,
+                                        int32_t G, int32_t c_lo, int32_t c_hi, int32_t c_lane,
+                                        unsigned &n_blocks)
+{
+    if (mn <= c_hi) {
+        if (COUNT) ++n_blocks;
+        if (mx <= c_lo) relax_update(acc, off, t, G);
+        else relax_update_lanes(acc, off, t, G, c_lane);
+    }
+}
+
+template <bool COUNT>
+__device__ __forceinline__ void relax8x2g(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnX,
+                                          int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mnY,
+                                          int32_t mxY, int32_t GY, int32_t c_lo, int32_t c_hi,
+                                          int32_t c_lane, unsigned &n_blocks)
+{
+    if (mnX <= c_hi || mnY <= c_hi) {
+        if (COUNT) n_blocks += (mnX <= c_hi ? 1 : 0) + (mnY <= c_hi ? 1 : 0);
+        if (mxX <= c_lo && mxY <= c_lo) {
+            relax_update2(acc, off, tX, GX, tY, GY);
+        } else {
+            // an entry above the lane's candidate (all of them in a half-column that has
+            // nothing even for c_hi) turns into +infinity for that lane
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int32_t sx = (tX[u] <= c_lane) ? tX[u] + GX : DEV_INF;
+                const int32_t sy = (tY[u] <= c_lane) ? tY[u] + GY : DEV_INF;
+                acc[off + u] = min(acc[off + u], min(sx, sy));
+            }
+        }
+    }
+}
+
 // Two candidates in one pass.  Where every device count a shape can still serve at this layer
 // lies in one window of 32 (d - 1 in [base, base + 32)), lanes 0..31 work for candidate 0 and
 // lanes 32..63 for candidate 1, both on that window: the scalar t_intra values are the same
@@ -214,7 +264,9 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // WIDE (with NC = 2): meshes of 65..128 devices.  One candidate per workgroup; the two
 // accumulator sets and the two LDS regions that otherwise belong to two candidates hold the
 // device counts 1..64 and 65..128 of the one candidate ("windows" 0 and 1).
-template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
+// GROUPED (with NC = 1): meshes of up to 32 devices, 64 / DP candidates per workgroup (see
+// relax8g above).
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false, bool GROUPED = false>
 __global__ __launch_bounds__(WAVE * NWK * WI)
 __attribute__((amdgpu_waves_per_eu((NC == 1 && WI == 1 && !DUMP && !WIDE) ? 7 : 4)))
 void recurrence_fast_kernel(
@@ -223,11 +275,12 @@ void recurrence_fast_kernel(
     unsigned long long *wave_relax, int64_t *chunk_min, int prune, int descending,
     int32_t *__restrict__ Fmin, int32_t *__restrict__ Sbest, int dummy_idx,
     int32_t *__restrict__ F_all, const int32_t *__restrict__ s_top_p,
-    const int32_t *__restrict__ group_min)
+    const int32_t *__restrict__ group_min, int group_dp)
 {
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     static_assert(!WIDE || (NC == 2 && WI == 1 && !DUMP), "two windows use the two-candidate layout");
-    constexpr int NCAND = WIDE ? 1 : NC;               // candidates per workgroup
+    static_assert(!GROUPED || (NC == 1 && WI == 1 && !DUMP && !WIDE), "lane groups: one-candidate form");
+    constexpr int NCAND = WIDE ? 1 : NC;               // candidates per workgroup (not GROUPED)
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
     constexpr int ROWS = KP + 6;                       // LDS rows per F layer (+ read-ahead slack)
@@ -263,7 +316,13 @@ void recurrence_fast_kernel(
     const bool half1 = lane >= 32;
     const int32_t size_of_lane = sizes[min(lane, S - 1)];   // lane q holds a_q (S <= 64)
     const int n = __builtin_amdgcn_readfirstlane(*n_cand_p);
-    const int n_groups = (n + NCAND - 1) / NCAND;
+    // GROUPED: lane = grp * DP + gl, group grp works for candidate j0 + grp on d - 1 = gl
+    // (DP: a power of two, D <= DP <= 64, chosen by the host)
+    const int DP = GROUPED ? group_dp : WAVE;
+    const int ncand = GROUPED ? WAVE / DP : NCAND;     // candidates per workgroup
+    const int gl = GROUPED ? (lane & (DP - 1)) : lane;
+    const int grp = GROUPED ? lane / DP : 0;
+    const int n_groups = (n + ncand - 1) / ncand;
     unsigned long long n_blocks_total = 0;
 
     for (;;) {
@@ -276,7 +335,7 @@ void recurrence_fast_kernel(
         const int tk = __builtin_amdgcn_readfirstlane(sh_tk[0]);
         __syncthreads();
         if (tk >= n_groups) break;                     // the workgroup's only exit
-        const int j0 = (descending ? (n_groups - 1 - tk) : tk) * NCAND;
+        const int j0 = (descending ? (n_groups - 1 - tk) : tk) * ncand;
         int jj[NC];                                    // candidate indices (the last may repeat;
         int32_t c[NC], c_given[NC];                    //  both windows serve one candidate)
 #pragma unroll
@@ -287,6 +346,16 @@ void recurrence_fast_kernel(
             // below); clamped so that the sentinel entries themselves never pass it
             c[e] = min(c_given[e], DEV_INF - 1);
         }
+        // GROUPED: every lane has its group's candidate; the scalar side works with the largest
+        const int jl = min(j0 + grp, n - 1);
+        int32_t c_lane_given = 0, c_lane = 0, c_lo = 0;
+        if constexpr (GROUPED) {
+            c_lane_given = cand[jl];
+            c_lane = min(c_lane_given, DEV_INF - 1);
+            c_lo = __builtin_amdgcn_readlane(c_lane, 0);         // candidates ascend with the group
+            c[0] = __builtin_amdgcn_readlane(c_lane, WAVE - 1);
+            c_given[0] = __builtin_amdgcn_readlane(c_lane_given, 0);   // decides the skip below
+        }
         if (prune) {
             // If the lowest candidate of the group may be skipped so may the others (their
             // evidence set is a superset and B * t_max is larger).  Wave 0's reading of the
@@ -296,10 +365,15 @@ void recurrence_fast_kernel(
             const int skip = __builtin_amdgcn_readfirstlane(sh_skip[0]);
             __syncthreads();
             if (skip) {
+                if constexpr (GROUPED) {
+                    Fmin[jl] = DEV_INF;                // every lane for its group's candidate
+                    Sbest[jl] = -1;
+                } else {
 #pragma unroll
-                for (int e = 0; e < NCAND; ++e) {
-                    Fmin[jj[e]] = DEV_INF;             // all threads, same value
-                    Sbest[jj[e]] = -1;
+                    for (int e = 0; e < NCAND; ++e) {
+                        Fmin[jj[e]] = DEV_INF;         // all threads, same value
+                        Sbest[jj[e]] = -1;
+                    }
                 }
                 continue;
             }
@@ -407,13 +481,19 @@ void recurrence_fast_kernel(
                     // F(0, K+1, 0) = 0 is the only finite operand: last layer K-1, d = a_q
 #pragma unroll
                     for (int e = 0; e < NC; ++e)
-                        G[e] = ((WIDE ? WAVE * e : 0) + lane + 1 == a) ? 0 : DEV_INF;
+                        G[e] = ((WIDE ? WAVE * e : 0) + gl + 1 == a) ? 0 : DEV_INF;
                     int i = i0;
                     for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, ++i) {
                         load_half(hA, pA);
                         load_half(hB, pB);
-                        relax8<NC, COUNT>(acc, 0, hA.t, mnA(hA), hA.mx, G, c, n_blocks);
-                        if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, mnB(hB), hB.mx, G, c, n_blocks);
+                        if constexpr (GROUPED) {
+                            relax8g<COUNT>(acc[0], 0, hA.t, hA.mn, hA.mx, G[0], c_lo, c[0], c_lane, n_blocks);
+                            if (i >= rowB)
+                                relax8g<COUNT>(acc[0], 8, hB.t, hB.mn, hB.mx, G[0], c_lo, c[0], c_lane, n_blocks);
+                        } else {
+                            relax8<NC, COUNT>(acc, 0, hA.t, mnA(hA), hA.mx, G, c, n_blocks);
+                            if (i >= rowB) relax8<NC, COUNT>(acc, 8, hB.t, mnB(hB), hB.mx, G, c, n_blocks);
+                        }
                     }
                 } else {
                 auto columns = [&](auto PK) {
@@ -429,7 +509,7 @@ void recurrence_fast_kernel(
                     constexpr bool P = decltype(PK)::value;
                     constexpr int NF = P ? 1 : NC;
                     const int dl = P ? pk_dl : lane;       // d - 1 served by this lane
-                    const bool live = dl >= a;             // d - a_q >= 1
+                    const bool live = (GROUPED ? gl : dl) >= a;   // d - a_q >= 1
                     // window 1 (WIDE): d - 1 = 64 + lane; its operand d - a_q lies in window 1
                     // for lane >= a_q, else in window 0 at lane 64 + lane - a_q
                     const bool live1 = WAVE + lane >= a;
@@ -448,6 +528,8 @@ void recurrence_fast_kernel(
                     auto relax = [&](int off, HalfColumn &h, int32_t mn) {
                         if constexpr (P)
                             relax8p<COUNT>(accP, off, h.t, mn, h.mx, G[0], c2, half1, n_blocks);
+                        else if constexpr (GROUPED)
+                            relax8g<COUNT>(acc[0], off, h.t, mn, h.mx, G[0], c_lo, c[0], c_lane, n_blocks);
                         else
                             relax8<NC, COUNT>(acc, off, h.t, mn, h.mx, G, c, n_blocks);
                     };
@@ -467,7 +549,10 @@ void recurrence_fast_kernel(
                             fence_loads();
                         };
                         auto compute2 = [&](Batch &b) {
-                            if constexpr (FOLD) {
+                            if constexpr (GROUPED) {
+                                relax8x2g<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
+                                                 mnf(b.Y), b.Y.mx, b.fY[0], c_lo, c[0], c_lane, n_blocks);
+                            } else if constexpr (FOLD) {
                                 // (runs with only the lanes that have an operand switched on)
                                 relax8x2<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
                                                 mnf(b.Y), b.Y.mx, b.fY[0], c[0], n_blocks);
@@ -645,23 +730,38 @@ void recurrence_fast_kernel(
         };
         if (s_top >= 1) layer(1, std::true_type{});
         for (int s = 2; s <= s_top; ++s) layer(s, std::false_type{});
+        if constexpr (GROUPED) {
+            // the lane of device count D in group grp holds F(s, first layer, all devices) of
+            // candidate j0 + grp; every other lane (and every wave but wave 0) stores to the
+            // spare slot
+            const bool owner = (wid == 0) && (gl == D - 1) && (j0 + grp < n);
+            const int slot = owner ? jl : dummy_idx;
+            Fmin[slot] = best[0];
+            Sbest[slot] = best[0] >= DEV_INF ? 0 : sbest[0];
+            // one atomic per candidate (the owner changes with the ticket: not a branch the
+            // persistent loop could be split on)
+            if (prune && owner && best[0] < DEV_INF)
+                atomicMin((long long *)&chunk_min[jl / PRUNE_CHUNK],
+                          (long long)best[0] + (long long)(p.B - 1) * (long long)c_lane_given);
+        } else {
         // lane D-1 (of window (D-1)/64) holds F(s, first layer, all devices); wave 0 owns the
-        // results; a repeated last candidate goes to the spare slot
+            // results; a repeated last candidate goes to the spare slot
 #pragma unroll
-        for (int e = 0; e < NCAND; ++e) {
-            const int32_t bv = (WIDE && D > WAVE) ? best[NC - 1] : best[e];
-            const int32_t sv = (WIDE && D > WAVE) ? sbest[NC - 1] : sbest[e];
-            const int32_t bestD = __builtin_amdgcn_readlane(bv, (D - 1) & (WAVE - 1));
-            const int32_t sD = __builtin_amdgcn_readlane(sv, (D - 1) & (WAVE - 1));
-            const bool owner = (wid == 0) && (j0 + e < n);
-            const int slot = owner ? jj[e] : dummy_idx;
-            Fmin[slot] = bestD;                        // all lanes, same value
-            Sbest[slot] = bestD >= DEV_INF ? 0 : sD;
-            if (prune) {                               // uniform; the minimum is idempotent
-                const long long T = (owner && bestD < DEV_INF)
-                                        ? (long long)bestD + (long long)(p.B - 1) * (long long)c_given[e]
-                                        : (long long)INF_I64;
-                atomicMin((long long *)&chunk_min[jj[e] / PRUNE_CHUNK], T);
+            for (int e = 0; e < NCAND; ++e) {
+                const int32_t bv = (WIDE && D > WAVE) ? best[NC - 1] : best[e];
+                const int32_t sv = (WIDE && D > WAVE) ? sbest[NC - 1] : sbest[e];
+                const int32_t bestD = __builtin_amdgcn_readlane(bv, (D - 1) & (WAVE - 1));
+                const int32_t sD = __builtin_amdgcn_readlane(sv, (D - 1) & (WAVE - 1));
+                const bool owner = (wid == 0) && (j0 + e < n);
+                const int slot = owner ? jj[e] : dummy_idx;
+                Fmin[slot] = bestD;                        // all lanes, same value
+                Sbest[slot] = bestD >= DEV_INF ? 0 : sD;
+                if (prune) {                               // uniform; the minimum is idempotent
+                    const long long T = (owner && bestD < DEV_INF)
+                                            ? (long long)bestD + (long long)(p.B - 1) * (long long)c_given[e]
+                                            : (long long)INF_I64;
+                    atomicMin((long long *)&chunk_min[jj[e] / PRUNE_CHUNK], T);
+                }
             }
         }
         if (COUNT) n_blocks_total += n_blocks;
@@ -680,20 +780,21 @@ static size_t fast_lds_bytes()
     return (size_t)NC * (NWK * 16 + 6) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
 }
 
-template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false>
+template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false, bool GROUPED = false>
 static hipError_t launch_one(hipStream_t st, const FastArgs &a, int grid)
 {
     const size_t lds = fast_lds_bytes<NWK, WI, NC>();
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(
-            (const void *)recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE>,
+            (const void *)recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE, GROUPED>,
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE>), dim3(grid),
+    hipLaunchKernelGGL((recurrence_fast_kernel<NWK, WI, NC, DUMP, COUNT, WIDE, GROUPED>), dim3(grid),
                        dim3(WAVE * NWK * WI), lds, st, a.p, a.recs,
                        a.sizes, a.cand, a.n_cand_p, a.ticket, a.wave_relax, a.chunk_min, a.prune,
-                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p, a.group_min);
+                       a.descending, a.Fmin, a.Sbest, a.dummy_idx, a.F_all, a.s_top_p, a.group_min,
+                       a.grouped);
     return hipGetLastError();
 }
 
@@ -704,10 +805,12 @@ static hipError_t launch_nwk(hipStream_t st, const FastArgs &a, int mode, int nc
     case FAST_MODE_PLAN: return launch_one<NWK, plan_wi(NWK), 1, true, false>(st, a, grid);
     case FAST_MODE_COUNT:
         if (a.p.D > WAVE) return launch_one<NWK, 1, 2, false, true, true>(st, a, grid);
+        if (a.grouped) return launch_one<NWK, 1, 1, false, true, false, true>(st, a, grid);
         return nc == 2 ? launch_one<NWK, 1, 2, false, true>(st, a, grid)
                        : launch_one<NWK, 1, 1, false, true>(st, a, grid);
     default:
         if (a.p.D > WAVE) return launch_one<NWK, 1, 2, false, false, true>(st, a, grid);
+        if (a.grouped) return launch_one<NWK, 1, 1, false, false, false, true>(st, a, grid);
         return nc == 2 ? launch_one<NWK, 1, 2, false, false>(st, a, grid)
                        : launch_one<NWK, 1, 1, false, false>(st, a, grid);
     }

@@ -173,7 +173,17 @@ struct FastArgs {
     int32_t *F_all;
     const int32_t *s_top_p;
     const int32_t *group_min;   // early-stop table (launch_repack_fast)
+    // batch modes, at most 32 devices, one-candidate form: 0, or the width DP of the lane groups
+    // (a power of two, D <= DP <= 32): 64 / DP candidates per workgroup
+    int grouped = 0;
 };
+// narrowest lane group that holds a mesh of D <= 32 devices
+inline int fast_lane_group_width(int D)
+{
+    int dp = 1;
+    while (dp < D) dp <<= 1;
+    return dp;
+}
 enum { FAST_MODE_BATCH = 0, FAST_MODE_COUNT = 1, FAST_MODE_PLAN = 2 };
 hipError_t launch_recurrence_fast(hipStream_t st, const FastArgs &a, int mode, int nc, int grid);
 int fast_kernel_blocks_per_cu(int K, int nc);

@@ -291,6 +291,65 @@ def test_create_checks_the_range_of_the_table_on_the_device():
     assert create_rc(allinf)[0] == 0
 
 
+LANE_GROUP_CASES = [  # seed, K, N, M: every group width 1, 2, 4, 8, 16, 32 and meshes that do
+    # not fill their group (3, 6, 10, 12, 24 devices)
+    (700, 9, 1, 1), (701, 20, 1, 2), (702, 14, 3, 1), (703, 33, 1, 4), (704, 25, 3, 2),
+    (705, 48, 1, 8), (706, 17, 5, 2), (707, 30, 3, 4), (708, 64, 2, 8), (709, 40, 3, 8),
+    (710, 22, 1, 32), (711, 64, 4, 8), (712, 100, 2, 16), (713, 70, 1, 4), (714, 5, 2, 16),
+]
+
+
+@pytest.mark.parametrize("prune", [False, True])
+@pytest.mark.parametrize("case", LANE_GROUP_CASES, ids=lambda c: f"s{c[0]}-K{c[1]}-{c[2]}x{c[3]}")
+def test_small_meshes_in_lane_groups(case, prune):
+    """On meshes of up to 32 devices the register/LDS kernel cuts the wave into groups of lanes
+    with a candidate each (64, 32, ... 2 candidates per workgroup).  Unstructured tables with a
+    narrow value range (neighbouring candidates then differ in few entries: the lane-by-lane
+    filter) and formula tables; every candidate, quantiles, and an unsorted caller list with
+    repeats whose length is no multiple of the group count; against the oracle, and against
+    the same kernel with the groups switched off."""
+    seed, K, N, M = case
+    rng = np.random.default_rng(seed)
+    if seed % 3 == 2:
+        w = W.deep_model_problem(seed, K, N, M)
+    else:
+        w = W.random_problem(seed, K, N, M, inf_frac=float(rng.choice([0.0, 0.2, 0.5])),
+                             value_hi=int(rng.choice([5, 60, 5000])))
+    allc = oracle.all_candidates(w.table, w.shapes)
+    if len(allc) == 0:
+        pytest.skip("no finite entry")
+    lists = [allc if len(allc) <= 400 else oracle.quantiles(allc, 397)]
+    hi = int(allc[-1]) + 3
+    lists.append(rng.integers(0, hi, size=int(rng.integers(1, 150))).astype(np.int32))
+    flags = B.ALPA_DP_PRUNE if prune else 0
+    h = B.alpa_dp_create(w.table, w.K, w.N, w.M, w.B, w.shapes)
+    try:
+        for cand in lists:
+            srt = np.unique(cand)
+            T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, srt, prune, 8)
+            by_value = dict(zip(srt.tolist(), T_ref.tolist()))
+            for groups in (64, 2):                  # as many as the mesh allows; two
+                B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_LANE_GROUPS, groups)
+                T, plan = B.alpa_dp_solve(h, cand, flags=flags)
+                assert T.tolist() == [by_value[int(c)] for c in cand]
+                _same_plan(plan, p_ref)
+            B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_LANE_GROUPS, 1)
+            T1, plan1 = B.alpa_dp_solve(h, cand, flags=flags)
+            assert (T1 == T).all() and plan1 == plan
+        # no list: the table's own values, all of them, with the library's own choice of groups
+        B.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_LANE_GROUPS, 0)
+        T_ref, p_ref = oracle.solve_parallel(w.table, w.N, w.M, w.B, w.shapes, allc, prune, 8)
+        T, plan = B.alpa_dp_solve(h, None, 0, flags)
+        assert (T == T_ref).all()
+        _same_plan(plan, p_ref)
+        plans = B.alpa_dp_solve_sweep(h, None, [1, 3, w.B], flags=flags)
+        for Bv, pl in zip([1, 3, w.B], plans):
+            _, pb = oracle.solve_parallel(w.table, w.N, w.M, Bv, w.shapes, allc, prune, 8)
+            _same_plan(pl, pb)
+    finally:
+        B.alpa_dp_destroy(h)
+
+
 def test_tuning_call_rejects_what_it_does_not_know():
     w = W.make_workload(1)
     L = B.load()
@@ -301,6 +360,9 @@ def test_tuning_call_rejects_what_it_does_not_know():
         assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_CANDIDATES_PER_WG, 3) == -1
         assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_DISTINCT_BY_SORT, 2) == -1
         assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_WG_PER_CU, -1) == -1
+        assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_LANE_GROUPS, 3) == -1
+        assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_LANE_GROUPS, 128) == -1
+        assert L.alpa_dp_set_tuning(h, B.ALPA_DP_TUNE_WORKGROUPS, -1) == -1
         ref = oracle.all_candidates(w.table, w.shapes)
         T_ref, p_ref = oracle.solve(w.table, w.N, w.M, w.B, w.shapes, ref, False)
         for key, value in ((B.ALPA_DP_TUNE_WG_PER_CU, 1), (B.ALPA_DP_TUNE_WG_PER_CU, 0),
