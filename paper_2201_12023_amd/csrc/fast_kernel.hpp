@@ -39,6 +39,9 @@ typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-loa
 
 constexpr int HB_INTS = 10;
 constexpr int END_SHAPES = 12;         // shapes covered by the early-stop table (3 registers)
+// Rows of an F layer in LDS beyond the KP first layers.  Three, not more: with 64 layers a
+// workgroup then takes 17152 + 3104 bytes of LDS and eight of them fit a compute unit.
+constexpr int FAST_ROWS_SLACK = 3;
 
 // Early-stop table: 8 groups of GW columns per (shape, half-block); GW = 8 up to 64 layers.
 constexpr int END_GROUPS = 8;
@@ -268,7 +271,7 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // relax8g above).
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false, bool GROUPED = false>
 __global__ __launch_bounds__(WAVE * NWK * WI)
-__attribute__((amdgpu_waves_per_eu((NC == 1 && WI == 1 && !DUMP && !WIDE) ? 7 : 4)))
+__attribute__((amdgpu_waves_per_eu((NC == 1 && WI == 1 && !DUMP && !WIDE && !GROUPED) ? 7 : 4)))
 void recurrence_fast_kernel(
     Problem p, const int32_t *__restrict__ recs_g, const int32_t *__restrict__ sizes_g,
     const int32_t *__restrict__ cand, const int32_t *__restrict__ n_cand_p, int32_t *ticket,
@@ -283,9 +286,11 @@ void recurrence_fast_kernel(
     constexpr int NCAND = WIDE ? 1 : NC;               // candidates per workgroup (not GROUPED)
     constexpr int NT = WAVE * NWK * WI;
     constexpr int KP = NWK * 16;
-    constexpr int ROWS = KP + 6;                       // LDS rows per F layer (+ read-ahead slack)
+    // LDS rows per F layer.  Column i reads row i + 1 <= K - 1 (layers s >= 2) and the loads run
+    // at most two columns ahead of the last one: rows up to K + 1, so KP + 2 rows would do.
+    constexpr int ROWS = KP + FAST_ROWS_SLACK;
     extern __shared__ int32_t lds[];                   // Fprev [NC][ROWS][64] (+ Fnext if WI > 1)
-    __shared__ int32_t sh_tk[NT];
+    __shared__ int32_t sh_tk[NWK * WI];
     __shared__ int32_t sh_skip[NWK * WI];
     // stage counts the early-stop table spans: 64, or 128 for more than 64 layers on more
     // than 64 devices (stage counts never exceed either)
@@ -308,8 +313,9 @@ void recurrence_fast_kernel(
     // candidate packing (two candidates, one pass): lane l works for candidate l / 32 on
     // device count d - 1 = pk_base + l % 32
     constexpr bool PACK = NC == 2 && WI == 1 && !DUMP && !WIDE;
-    // one candidate per workgroup: two columns folded into one three-operand minimum per row
-    constexpr bool FOLD = NC == 1 && WI == 1 && !DUMP && !WIDE;
+    // one candidate per workgroup (batch and plan runs): two columns folded into one
+    // three-operand minimum per row
+    constexpr bool FOLD = NC == 1 && !WIDE;
     const int pk_base = max(0, D - 32);
     const int pk_dl = pk_base + (lane & 31);
     const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
@@ -330,7 +336,8 @@ void recurrence_fast_kernel(
         // 0's return value.  No branch on the thread id may appear in this loop: it would be
         // loop-invariant, the compiler splits the loop on it, and the lanes of one wave then
         // run the persistent loop out of step with each other.
-        sh_tk[tid] = atomicAdd(ticket, tid == 0 ? 1 : 0);
+        // (each wave parks its first lane's return value; wave 0's first lane is thread 0)
+        sh_tk[wid] = __builtin_amdgcn_readfirstlane(atomicAdd(ticket, tid == 0 ? 1 : 0));
         __syncthreads();
         const int tk = __builtin_amdgcn_readfirstlane(sh_tk[0]);
         __syncthreads();
@@ -777,7 +784,7 @@ constexpr int plan_wi(int NWK) { return NWK > 4 ? 2 : 4; }
 template <int NWK, int WI, int NC>
 static size_t fast_lds_bytes()
 {
-    return (size_t)NC * (NWK * 16 + 6) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
+    return (size_t)NC * (NWK * 16 + FAST_ROWS_SLACK) * WAVE * sizeof(int32_t) * (WI > 1 ? 2 : 1);
 }
 
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false, bool GROUPED = false>
