@@ -122,7 +122,13 @@ def equal_layer_table(table) -> np.ndarray:
 _lib_cluster = None
 
 
-def cluster(flop, src, dst, nbytes, L: int, delta_ppm: int):
+def cluster_exact(flop, src, dst, nbytes, L: int, delta_ppm: int):
+    """Operator clustering (Eq. 6) with the tie-break over whole clusterings: the smallest sum
+    of squared per-layer FLOP among all clusterings that reach the optimal G."""
+    return cluster(flop, src, dst, nbytes, L, delta_ppm, _fn="orc_cluster_exact")
+
+
+def cluster(flop, src, dst, nbytes, L: int, delta_ppm: int, _fn: str = "orc_cluster"):
     """Operator clustering (Eq. 6).  Returns (G, V, first_op list of L + 1) or (INF64, 0, [])."""
     global _lib_cluster
     if _lib_cluster is None:
@@ -135,11 +141,11 @@ def cluster(flop, src, dst, nbytes, L: int, delta_ppm: int):
     assert src.size == dst.size == nbytes.size
     G, V = ctypes.c_int64(), ctypes.c_int64()
     first = np.zeros(int(L) + 1, dtype=np.int32)
-    rc = _lib_cluster.orc_cluster(_i32p(flop), _i32p(src), _i32p(dst), _i64p(nbytes),
-                                  int(src.size), int(flop.size), int(L), int(delta_ppm),
-                                  ctypes.byref(G), ctypes.byref(V), _i32p(first))
+    rc = getattr(_lib_cluster, _fn)(_i32p(flop), _i32p(src), _i32p(dst), _i64p(nbytes),
+                                    int(src.size), int(flop.size), int(L), int(delta_ppm),
+                                    ctypes.byref(G), ctypes.byref(V), _i32p(first))
     if rc != 0:
-        raise RuntimeError(f"orc_cluster failed: {rc}")
+        raise RuntimeError(f"{_fn} failed: {rc}")
     if G.value == INF64:
         return INF64, 0, []
     return int(G.value), int(V.value), [int(x) for x in first]

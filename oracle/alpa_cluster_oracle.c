@@ -34,6 +34,17 @@
  * Operators are 0-based in the arrays: first_op[r] is the first operator of
  * layer r, first_op[L] = K.
  *
+ * A second function, orc_cluster_exact, takes the closing sentence of that
+ * paragraph literally instead: among ALL clusterings that reach the optimal
+ * G(K, L), the one with the smallest sum of squared per-layer FLOP.  It is the
+ * recurrence run twice: first for G alone, then, with G* = G(K, L) known,
+ *     W(k, r) = min over 1 <= i <= k with the FLOP bound and C(i, k) <= G*
+ *               of W(i - 1, r - 1) + FLOP(o_i..o_k)^2,
+ * lowest i on ties (a clustering reaches G* exactly when none of its layers
+ * receives more than G*, since no clustering stays below it).  Pinned by the
+ * enumeration (both components and the clustering itself) and by an example
+ * worked by hand in the test, on which the two functions differ.
+ *
  * Parity pins (tests marked "not gpu"): a hand-worked example stored under
  * tests/golden/, enumeration of every clustering for K <= 10 (the first
  * component is the true optimum; on chain graphs, where every cut costs the
@@ -114,5 +125,85 @@ int orc_cluster(const int32_t *flop, const int32_t *src, const int32_t *dst,
         }
     }
     free(C); free(G); free(V); free(A);
+    return 0;
+}
+
+/* Eq. 6 with its tie-break taken over whole clusterings: (G*, smallest sum of squares among the
+ * clusterings that reach G*, that clustering).  Same arguments and limits as orc_cluster. */
+int orc_cluster_exact(const int32_t *flop, const int32_t *src, const int32_t *dst,
+                      const int64_t *bytes, int E, int K, int L, int delta_ppm,
+                      int64_t *out_G, int64_t *out_V, int32_t *first_op)
+{
+    if (K < 1 || L < 1 || delta_ppm < 0 || E < 0) return -1;
+    int64_t total = 0;
+    for (int k = 0; k < K; ++k) {
+        if (flop[k] < 0) return -1;
+        total += flop[k];
+    }
+    if (total >= ((int64_t)1 << 31)) return -1;
+    if (total * (int64_t)L >= ((int64_t)1 << 42)) return -1;
+    for (int e = 0; e < E; ++e)
+        if (src[e] < 0 || dst[e] >= K || src[e] >= dst[e] || bytes[e] < 0) return -1;
+
+    const size_t W = (size_t)K + 1;
+    int64_t *C = malloc(W * W * sizeof(int64_t));
+    int64_t *G = malloc((size_t)(L + 1) * W * sizeof(int64_t));   /* first G, then W */
+    int32_t *A = malloc((size_t)(L + 1) * W * sizeof(int32_t));
+    if (!C || !G || !A) { free(C); free(G); free(A); return -2; }
+    for (int i = 1; i <= K; ++i)
+        for (int k = i; k <= K; ++k) C[i * W + k] = comm_in(src, dst, bytes, E, i, k);
+    /* first run: G(k, r) alone */
+    for (int r = 0; r <= L; ++r)
+        for (int k = 0; k <= K; ++k) G[r * W + k] = ORC_INF64;
+    G[0] = 0;
+    for (int r = 1; r <= L; ++r)
+        for (int k = 1; k <= K; ++k) {
+            int64_t bg = ORC_INF64;
+            for (int i = 1; i <= k; ++i) {
+                int64_t f = 0;
+                for (int x = i; x <= k; ++x) f += flop[x - 1];
+                if (f * (int64_t)L * 1000000 > ((int64_t)1000000 + delta_ppm) * total) continue;
+                const int64_t gp = G[(r - 1) * W + (i - 1)];
+                if (gp == ORC_INF64) continue;
+                const int64_t c = C[i * W + k];
+                const int64_t g = gp > c ? gp : c;
+                if (g < bg) bg = g;
+            }
+            G[r * W + k] = bg;
+        }
+    const int64_t gstar = G[L * W + K];
+    *out_G = gstar;
+    *out_V = 0;
+    if (gstar != ORC_INF64) {
+        /* second run: smallest sum of squares with every layer receiving at most G* */
+        for (int r = 0; r <= L; ++r)
+            for (int k = 0; k <= K; ++k) { G[r * W + k] = ORC_INF64; A[r * W + k] = 0; }
+        G[0] = 0;
+        for (int r = 1; r <= L; ++r)
+            for (int k = 1; k <= K; ++k) {
+                int64_t bw = ORC_INF64;
+                int bi = 0;
+                for (int i = 1; i <= k; ++i) {
+                    int64_t f = 0;
+                    for (int x = i; x <= k; ++x) f += flop[x - 1];
+                    if (f * (int64_t)L * 1000000 > ((int64_t)1000000 + delta_ppm) * total) continue;
+                    if (C[i * W + k] > gstar) continue;
+                    const int64_t wp = G[(r - 1) * W + (i - 1)];
+                    if (wp == ORC_INF64) continue;
+                    const int64_t w = wp + f * f;
+                    if (w < bw) { bw = w; bi = i; }
+                }
+                G[r * W + k] = bw; A[r * W + k] = bi;
+            }
+        *out_V = G[L * W + K];
+        int k = K;
+        first_op[L] = K;
+        for (int r = L; r >= 1; --r) {
+            const int i = A[r * W + k];
+            first_op[r - 1] = i - 1;
+            k = i - 1;
+        }
+    }
+    free(C); free(G); free(A);
     return 0;
 }
