@@ -288,6 +288,22 @@ int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
                         int32_t *out_first_op, float *out_ms);
 
 /*
+ * The same clustering with the tie-break of Eq. 6's closing sentence ("if there are multiple
+ * solutions with the same communication cost, choose the one with the most uniform structure
+ * by also minimising the variance of per-layer FLOP") taken over whole clusterings instead of
+ * cell by cell: *out_comm is the same G(K, L); *out_sumsq is the smallest sum of squared
+ * per-layer FLOP among ALL clusterings that reach it (never larger than alpa_cluster_layers's),
+ * and out_first_op is that clustering (among several, the one whose last layer starts
+ * earliest, then whose last but one does, and so on).  Two runs of the recurrence: G alone,
+ * then W(k, r) = min over i with the FLOP bound and C(i, k) <= G(K, L) of
+ * W(i-1, r-1) + FLOP(o_i..o_k)^2.  Arguments, limits and errors as for alpa_cluster_layers.
+ */
+int alpa_cluster_layers_exact(const int32_t *flop, int K, const int32_t *edge_src,
+                              const int32_t *edge_dst, const int64_t *edge_bytes, int num_edges,
+                              int L, int delta_ppm, int64_t *out_comm, int64_t *out_sumsq,
+                              int32_t *out_first_op, float *out_ms);
+
+/*
  * alpa_cluster_layers for callers that cannot allocate device memory or wait: code recorded into
  * a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same computation and
  * results; inputs and outputs are DEVICE pointers owned by the caller, the call only queues

@@ -36,7 +36,7 @@ SYMBOLS = ["alpa_dp_create", "alpa_dp_create_from_profiles", "alpa_dp_get_table"
            "alpa_dp_solve", "alpa_dp_solve_dev", "alpa_dp_solve_sweep", "alpa_dp_candidates",
            "alpa_dp_best",
            "alpa_dp_last_timing", "alpa_dp_last_counters", "alpa_dp_destroy",
-           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_cluster_layers_static", "alpa_place_submeshes", "alpa_dp_measure_valu_peak"]
+           "alpa_dp_last_error", "alpa_cluster_layers", "alpa_cluster_layers_exact", "alpa_cluster_layers_static", "alpa_place_submeshes", "alpa_dp_measure_valu_peak"]
 
 
 class alpa_shape_t(ctypes.Structure):
@@ -102,6 +102,7 @@ def load():
     L.alpa_cluster_layers.argtypes = [vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, i64p, i64p, vp,
                                       ctypes.POINTER(ctypes.c_float)]
+    L.alpa_cluster_layers_exact.argtypes = L.alpa_cluster_layers.argtypes
     L.alpa_cluster_layers_static.argtypes = [vp, ctypes.c_int, vp, vp, vp, ctypes.c_int,
                                              ctypes.c_int, ctypes.c_int, vp, vp, vp]
     L.alpa_place_submeshes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(alpa_shape_t),
@@ -266,7 +267,14 @@ def plan_from_bytes(buf: bytes) -> dict:
 PLAN_BYTES = ctypes.sizeof(alpa_plan_t)
 
 
-def alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm):
+def alpa_cluster_layers_exact(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm):
+    """Operator clustering with the variance tie-break taken over whole clusterings."""
+    return alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm,
+                               _fn="alpa_cluster_layers_exact")
+
+
+def alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm,
+                        _fn="alpa_cluster_layers"):
     """Operator clustering (Eq. 6).  Host arrays in; returns dict(comm, sumsq, first_op, ms);
     comm == INF_I64 and first_op == [] if no clustering satisfies the FLOP bound."""
     lib = load()
@@ -278,7 +286,7 @@ def alpa_cluster_layers(flop, edge_src, edge_dst, edge_bytes, L, delta_ppm):
         raise ValueError("edge arrays must have one length")
     comm, sumsq, ms = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_float()
     first = np.zeros(max(int(L), 0) + 1, dtype=np.int32)
-    _check(lib.alpa_cluster_layers(f.ctypes.data, int(f.size), s.ctypes.data if s.size else None,
+    _check(getattr(lib, _fn)(f.ctypes.data, int(f.size), s.ctypes.data if s.size else None,
                                    d.ctypes.data if s.size else None,
                                    b.ctypes.data if s.size else None, int(s.size), int(L),
                                    int(delta_ppm), ctypes.byref(comm), ctypes.byref(sumsq),

@@ -30,10 +30,10 @@ int fail(int code, const std::string &msg) { return alpa_dp_set_error_(code, msg
 
 }  // namespace
 
-extern "C" int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
-                                   const int32_t *edge_dst, const int64_t *edge_bytes,
-                                   int num_edges, int L, int delta_ppm, int64_t *out_comm,
-                                   int64_t *out_sumsq, int32_t *out_first_op, float *out_ms)
+static int cluster_layers_impl(const int32_t *flop, int K, const int32_t *edge_src,
+                               const int32_t *edge_dst, const int64_t *edge_bytes, int num_edges,
+                               int L, int delta_ppm, int64_t *out_comm, int64_t *out_sumsq,
+                               int32_t *out_first_op, float *out_ms, int exact)
 {
     if (!flop || !out_comm || !out_sumsq || !out_first_op)
         return fail(ALPA_DP_EINVAL, "null argument");
@@ -90,7 +90,8 @@ extern "C" int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *ed
     HIPCHK(launch_cluster(st, d_flop.as<int32_t>(), d_src.as<int32_t>(), d_dst.as<int32_t>(),
                           d_nb.as<int64_t>(), num_edges, K, L, cap, d_Ct.as<int64_t>(),
                           d_chunk.as<int64_t>(), d_pf.as<int64_t>(), d_GV.as<int64_t>(),
-                          d_arg.as<int32_t>(), d_out.as<int64_t>(), d_first.as<int32_t>()));
+                          d_arg.as<int32_t>(), d_out.as<int64_t>(), d_first.as<int32_t>(), nullptr, 0,
+                          exact));
     HIPCHK(hipEventRecord(ev1, st));
     int64_t res[2] = {0, 0};
     HIPCHK(hipMemcpyAsync(res, d_out.p, sizeof(res), hipMemcpyDeviceToHost, st));
@@ -100,6 +101,24 @@ extern "C" int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *ed
     *out_sumsq = res[1];
     if (out_ms) HIPCHK(hipEventElapsedTime(out_ms, ev0, ev1));
     return ALPA_DP_OK;
+}
+
+extern "C" int alpa_cluster_layers(const int32_t *flop, int K, const int32_t *edge_src,
+                                   const int32_t *edge_dst, const int64_t *edge_bytes,
+                                   int num_edges, int L, int delta_ppm, int64_t *out_comm,
+                                   int64_t *out_sumsq, int32_t *out_first_op, float *out_ms)
+{
+    return cluster_layers_impl(flop, K, edge_src, edge_dst, edge_bytes, num_edges, L, delta_ppm,
+                               out_comm, out_sumsq, out_first_op, out_ms, 0);
+}
+
+extern "C" int alpa_cluster_layers_exact(const int32_t *flop, int K, const int32_t *edge_src,
+                                         const int32_t *edge_dst, const int64_t *edge_bytes,
+                                         int num_edges, int L, int delta_ppm, int64_t *out_comm,
+                                         int64_t *out_sumsq, int32_t *out_first_op, float *out_ms)
+{
+    return cluster_layers_impl(flop, K, edge_src, edge_dst, edge_bytes, num_edges, L, delta_ppm,
+                               out_comm, out_sumsq, out_first_op, out_ms, 1);
 }
 
 // ---------------------------------------------------------------- no allocation on the call

@@ -218,12 +218,13 @@ hipError_t launch_init_best_plan(hipStream_t st, void *best_plan);
 // GV [4*(K+1)] (int64), arg [L*(K+1)], out [2] (G, V), first_op [L+1].  ctl == nullptr: the
 // caller has checked the inputs and passes the FLOP bound `cap`.  ctl != nullptr ([2] int64):
 // the inputs are checked and the bound is computed from delta_ppm on the device, out is [3]
-// (G, V, status) and `cap` is ignored.
+// (G, V, status) and `cap` is ignored.  exact != 0 (host-checked inputs only): a second run of
+// the recurrence minimises V over every clustering that reaches G(K, L).
 hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *src,
                           const int32_t *dst, const int64_t *nbytes, int E, int K, int L,
                           int64_t cap, int64_t *Ct, int64_t *chunk, int64_t *pf, int64_t *GV,
                           int32_t *arg, int64_t *out, int32_t *first_op, int64_t *ctl = nullptr,
-                          int delta_ppm = 0);
+                          int delta_ppm = 0, int exact = 0);
 size_t cluster_chunk_rows(int K);
 
 }  // namespace alpa

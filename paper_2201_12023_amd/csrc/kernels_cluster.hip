@@ -256,17 +256,71 @@ __global__ __launch_bounds__(256) void cluster_layer_kernel(
     if (lane == 0 && n == 1) { Gn[0] = INF_I64; Vn[0] = 0; arg[0] = 0; }   // G(0, r > 0)
 }
 
+// Second run of the exact mode (the variance tie-break over whole clusterings): with
+// G* = G(K, L) of the first run in *gstar_p,
+//   W(n, r) = min over the feasible i with C(i, n) <= G* of W(i-1, r-1) + FLOP(o_i..o_n)^2,
+// lowest i on ties.  Same mapping as cluster_layer_kernel.
+__global__ __launch_bounds__(256) void cluster_layer_exact_kernel(
+    const int64_t *__restrict__ Ct, const int64_t *__restrict__ pf, int K, int64_t cap,
+    const int64_t *__restrict__ gstar_p, const int64_t *__restrict__ Wp,
+    int64_t *__restrict__ Wn, int32_t *__restrict__ arg)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6) + 1;
+    if (n > K) return;                                              // whole wave
+    const int64_t gstar = *gstar_p;
+    const int64_t need = pf[n] - cap;
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (pf[mid] >= need) hi = mid; else lo = mid + 1;
+    }
+    const int i_min = lo + 1;
+    Lex best{INF_I64, 0, 0};                                        // (W, unused, i)
+    const int64_t *row = Ct + (size_t)(n - 1) * K;
+    if (gstar != INF_I64) {
+        for (int i = i_min + lane; i <= n; i += WAVE) {
+            const int64_t wp = Wp[i - 1];
+            if (wp == INF_I64 || row[i - 1] > gstar) continue;
+            const int64_t f = pf[n] - pf[i - 1];
+            const Lex cur{wp + f * f, 0, i};
+            if (lex_less(cur, best)) best = cur;
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) {
+        const Lex o = lex_shfl_xor(best, m);
+        if (lex_less(o, best)) best = o;
+    }
+    if (best.g == INF_I64) best.i = 0;
+    Wn[n] = best.g;                                                 // all lanes, same value
+    arg[n] = best.i;
+    if (lane == 0 && n == 1) { Wn[0] = INF_I64; arg[0] = 0; }       // W(0, r > 0)
+}
+
+// keep[0] = G(K, L) of the first run; W(., 0) for the second: only the empty prefix is finite
+__global__ void cluster_begin_exact_kernel(const int64_t *__restrict__ G, int K,
+                                           int64_t *__restrict__ keep, int64_t *__restrict__ W0)
+{
+    const int64_t g = G[K];                                         // read before W0 may alias it
+    __syncthreads();
+    for (int x = threadIdx.x; x <= K; x += blockDim.x) W0[x] = (x == 0) ? 0 : INF_I64;
+    if (threadIdx.x == 0) keep[0] = g;
+}
+
 // out[0] = G(K, L), out[1] = V(K, L); first_op[0..L] by walking arg back (one thread).  With
 // ctl (device-resident inputs) also out[2] = ctl[0], the status of the argument checks, and
 // "no clustering" is reported if that is not 0.
 __global__ void cluster_walk_kernel(const int64_t *__restrict__ G, const int64_t *__restrict__ V,
                                     const int32_t *__restrict__ arg, int K, int L,
                                     const int64_t *__restrict__ ctl, int64_t *__restrict__ out,
-                                    int32_t *__restrict__ first_op)
+                                    int32_t *__restrict__ first_op,
+                                    const int64_t *__restrict__ gstar_p)
 {
+    // gstar_p (exact mode): the first component is *gstar_p and V is the second run's W row
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
     if (ctl) out[2] = ctl[0];
-    const int64_t g = (ctl && ctl[0] != 0) ? INF_I64 : G[K];
+    const int64_t g = (ctl && ctl[0] != 0) ? INF_I64 : (gstar_p ? *gstar_p : G[K]);
     out[0] = g;
     out[1] = g == INF_I64 ? 0 : V[K];
     if (g == INF_I64) {
@@ -286,7 +340,7 @@ hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *sr
                           const int32_t *dst, const int64_t *nbytes, int E, int K, int L,
                           int64_t cap, int64_t *Ct, int64_t *chunk, int64_t *pf, int64_t *GV,
                           int32_t *arg, int64_t *out, int32_t *first_op, int64_t *ctl,
-                          int delta_ppm)
+                          int delta_ppm, int exact)
 {
     if (ctl)
         hipLaunchKernelGGL(cluster_check_kernel, dim3(1), dim3(1024), 0, st, flop, K, src, dst,
@@ -315,8 +369,24 @@ hipError_t launch_cluster(hipStream_t st, const int32_t *flop, const int32_t *sr
                            (const int64_t *)ctl, G[p], V[p], G[c], V[c],
                            arg + (size_t)(r - 1) * (K + 1));
     }
+    if (exact) {
+        // second run over the V rows (the first run's V values are not needed any more);
+        // G* is parked in the G row that the first run wrote last but one
+        int64_t *keep = G[(L & 1) ^ 1];
+        hipLaunchKernelGGL(cluster_begin_exact_kernel, dim3(1), dim3(256), 0, st, G[L & 1], K, keep,
+                           V[0]);
+        for (int r = 1; r <= L; ++r) {
+            const int p = (r - 1) & 1, c = r & 1;
+            hipLaunchKernelGGL(cluster_layer_exact_kernel, dim3((K + 3) / 4), dim3(256), 0, st, Ct,
+                               pf, K, cap, (const int64_t *)keep, V[p], V[c],
+                               arg + (size_t)(r - 1) * (K + 1));
+        }
+        hipLaunchKernelGGL(cluster_walk_kernel, dim3(1), dim3(WAVE), 0, st, V[L & 1], V[L & 1], arg,
+                           K, L, (const int64_t *)ctl, out, first_op, (const int64_t *)keep);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(cluster_walk_kernel, dim3(1), dim3(WAVE), 0, st, G[L & 1], V[L & 1], arg, K, L,
-                       (const int64_t *)ctl, out, first_op);
+                       (const int64_t *)ctl, out, first_op, (const int64_t *)nullptr);
     return hipGetLastError();
 }
 

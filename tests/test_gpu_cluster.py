@@ -15,7 +15,28 @@ def _same(g, L, delta):
     ref = oracle.cluster(g.flop, g.src, g.dst, g.nbytes, L, delta)
     got = B.alpa_cluster_layers(g.flop, g.src, g.dst, g.nbytes, L, delta)
     assert (got["comm"], got["sumsq"], got["first_op"]) == ref, (g.K, L, delta)
+    # the variance tie-break over whole clusterings, against its own oracle function
+    ref_x = oracle.cluster_exact(g.flop, g.src, g.dst, g.nbytes, L, delta)
+    got_x = B.alpa_cluster_layers_exact(g.flop, g.src, g.dst, g.nbytes, L, delta)
+    assert (got_x["comm"], got_x["sumsq"], got_x["first_op"]) == ref_x, (g.K, L, delta)
+    assert got_x["comm"] == got["comm"] and got_x["sumsq"] <= got["sumsq"]
     return got
+
+
+def test_exact_tie_break_example_on_the_device():
+    """The example worked by hand in tests/test_cluster_oracle_pins.py: the two rules differ."""
+    args = ([1, 4, 4, 3], [1, 0, 1], [3, 3, 2], [2, 2, 1], 3, 10**9)
+    got = B.alpa_cluster_layers_exact(*args)
+    assert (got["comm"], got["sumsq"], got["first_op"]) == (4, 50, [0, 2, 3, 4])
+    got = B.alpa_cluster_layers(*args)
+    assert (got["comm"], got["sumsq"], got["first_op"]) == (4, 74, [0, 1, 3, 4])
+    n = 0
+    for seed in range(60):                         # graphs on which the two rules often differ
+        g = W.random_op_graph(900 + seed, 9, 20, flop_hi=5, bytes_hi=3)
+        for L in (3, 4, 5):
+            _same(g, L, 10**9)
+            n += 1
+    assert n == 180
 
 
 def test_hand_worked_example_on_the_device():
@@ -81,6 +102,8 @@ def test_largest_size_by_properties():
 def test_infeasible_and_limits():
     g = W.random_op_graph(3, 10, 20)
     got = B.alpa_cluster_layers(g.flop, g.src, g.dst, g.nbytes, 11, 10**9)     # L > K
+    assert got["comm"] == INF64 and got["first_op"] == [] and got["sumsq"] == 0
+    got = B.alpa_cluster_layers_exact(g.flop, g.src, g.dst, g.nbytes, 11, 10**9)
     assert got["comm"] == INF64 and got["first_op"] == [] and got["sumsq"] == 0
     flop = np.asarray([1, 1, 50, 1, 1, 1], np.int32)
     e = np.arange(5, dtype=np.int32)
