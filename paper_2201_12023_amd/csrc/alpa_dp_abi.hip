@@ -277,7 +277,6 @@ static int create_on_device(alpa_dp *h, const std::vector<int32_t> &sizes, FillT
         h->KP = 16 * ((K + 15) / 16);
         HIPCHK(hipMalloc(&h->d_recs, fast_table_ints(K, S) * 4));
         HIPCHK(hipMalloc(&h->d_gmin, fast_group_min_ints(K, D, S) * 4));
-        HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
         HIPCHK(launch_repack_fast(h->stream, h->d_table, K, D, S, h->KP, h->d_recs, h->d_gmin));
         for (int nc = 1; nc <= 2; ++nc) {
             int per_cu = fast_kernel_blocks_per_cu(K, nc);
@@ -414,7 +413,6 @@ extern "C" int alpa_dp_restrict_equal_layers(alpa_dp_t *h)
     const int K = h->p.K, D = h->p.D, S = h->p.S;
     HIPCHK(launch_equal_layer_mask(h->stream, h->d_table, K, S));
     if (h->fast_ok) {
-        HIPCHK(hipMemsetAsync(h->d_recs, 0x3f, fast_table_ints(K, S) * 4, h->stream));
         HIPCHK(launch_repack_fast(h->stream, h->d_table, K, D, S, h->KP, h->d_recs, h->d_gmin));
     }
     // the candidate list changes with the table; the running best belonged to the old one

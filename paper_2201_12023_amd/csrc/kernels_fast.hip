@@ -61,9 +61,19 @@ __global__ void repack_group_min_kernel(int K, int S, int KP, int SW, const int3
     }
 }
 
+// the records past the last column, which the loads that run ahead may touch: +infinity
+__global__ void repack_padding_kernel(int32_t *__restrict__ p, int n)
+{
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < n; x += gridDim.x * blockDim.x)
+        p[x] = DEV_INF;
+}
+
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int D, int S, int KP,
                               int32_t *recs, int32_t *group_min)
 {
+    const int rec_ints = (KP / 8) * HB_INTS;
+    hipLaunchKernelGGL(repack_padding_kernel, dim3(8), dim3(256), 0, st,
+                       recs + (size_t)K * S * K * rec_ints, 32 * rec_ints);
     long long total = (long long)K * K * S * (KP / 8);
     int grid = (int)((total + 255) / 256);
     if (grid > 8192) grid = 8192;

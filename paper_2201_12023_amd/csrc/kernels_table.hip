@@ -110,15 +110,12 @@ __global__ void set_i32_kernel(int32_t *p, int32_t v)
 __global__ __launch_bounds__(256) void table_range_kernel(const int32_t *__restrict__ table, int K,
                                                           int S, int32_t *__restrict__ out)
 {
-    const long long total = (long long)K * K * K * S;
+    // one block per (s, first layer k): its used entries, last layers k..K-1, are contiguous
+    const int k = blockIdx.x % K;
+    const int32_t *row = table + (size_t)blockIdx.x * K * S;
     int32_t mn = INF_I32, mx = -1;
-    for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
-         e += (long long)gridDim.x * blockDim.x) {
-        long long r = e / S;
-        const int i = (int)(r % K); r /= K;
-        const int k = (int)(r % K);
-        if (i < k) continue;
-        const int32_t t = table[e];
+    for (int x = k * S + threadIdx.x; x < K * S; x += blockDim.x) {
+        const int32_t t = row[x];
         mn = min(mn, t);
         if (t != INF_I32) mx = max(mx, t);
     }
@@ -134,9 +131,7 @@ hipError_t launch_table_range(hipStream_t st, const int32_t *table, int K, int S
 {
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(WAVE), 0, st, out + 0, INF_I32);
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(WAVE), 0, st, out + 1, -1);
-    const long long total = (long long)K * K * K * S;
-    const int grid = (int)std::min<long long>((total + 255) / 256, 2048);
-    hipLaunchKernelGGL(table_range_kernel, dim3(grid), dim3(256), 0, st, table, K, S, out);
+    hipLaunchKernelGGL(table_range_kernel, dim3(K * K), dim3(256), 0, st, table, K, S, out);
     return hipGetLastError();
 }
 

@@ -38,6 +38,15 @@ int main() {
         alpa_plan_t plan;
         CK(alpa_dp_solve(h, nullptr, 0, 0, T.data(), &plan));
         CK(alpa_dp_solve(h, nullptr, 0, ALPA_DP_PRUNE, T.data(), &plan));
+        for (int key_value : {ALPA_DP_TUNE_CANDIDATES_PER_WG * 16 + 2, ALPA_DP_TUNE_CANDIDATES_PER_WG * 16 + 0,
+                              ALPA_DP_TUNE_DISTINCT_BY_SORT * 16 + 1, ALPA_DP_TUNE_DISTINCT_BY_SORT * 16 + 0,
+                              ALPA_DP_TUNE_LANE_GROUPS * 16 + 1, ALPA_DP_TUNE_LANE_GROUPS * 16 + 4,
+                              ALPA_DP_TUNE_LANE_GROUPS * 16 + 0, ALPA_DP_TUNE_WG_PER_CU * 16 + 1,
+                              ALPA_DP_TUNE_WG_PER_CU * 16 + 0, ALPA_DP_TUNE_WORKGROUPS * 16 + 3,
+                              ALPA_DP_TUNE_WORKGROUPS * 16 + 0}) {
+            CK(alpa_dp_set_tuning(h, key_value / 16, key_value % 16));
+            CK(alpa_dp_solve(h, nullptr, 0, ALPA_DP_PRUNE, T.data(), &plan));
+        }
         if (n >= 2) CK(alpa_dp_solve(h, nullptr, 2, ALPA_DP_GENERIC, T.data(), &plan));
         std::vector<int32_t> cand = {5, 500, 17, 17, 250, 0, 499};
         std::vector<int64_t> T2(cand.size());
@@ -53,6 +62,7 @@ int main() {
         float a, b, d; CK(alpa_dp_last_timing(h, &a, &b, &d));
         int nc; int64_t wr; CK(alpa_dp_last_counters(h, &nc, &wr));
         CK(alpa_dp_set_B(h, 7));
+        CK(alpa_dp_best(h, &plan));                 // no solve since the change of B: solves itself
         std::vector<int32_t> back(tab.size());
         CK(alpa_dp_get_table(h, back.data()));
         CK(alpa_dp_restrict_equal_layers(h));
@@ -84,6 +94,7 @@ int main() {
             if (L > K) continue;
             int64_t comm, sq; std::vector<int32_t> first(L + 1); float ms;
             CK(alpa_cluster_layers(flop.data(), K, es.data(), ed.data(), eb.data(), (int)es.size(), L, 500000, &comm, &sq, first.data(), &ms));
+            CK(alpa_cluster_layers_exact(flop.data(), K, es.data(), ed.data(), eb.data(), (int)es.size(), L, 500000, &comm, &sq, first.data(), &ms));
         }
     }
     double pk; CK(alpa_dp_measure_valu_peak(&pk));
