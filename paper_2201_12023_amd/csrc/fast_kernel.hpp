@@ -20,14 +20,17 @@
 // Infinite entries need no filter: DEV_INF + anything >= DEV_INF and accumulators start at
 // DEV_INF.  Column loads (scalars and the LDS row) are issued one column ahead.
 //
-// Table layout (built once per handle by repack_fast_kernel): one record per column
-// (s-1, q, i), columns in that order (i fastest); a record is KP/8 half-block entries of
-// HB_INTS = 10 int32 (KP = 16 * ceil(K/16)):
-//   {min, max over the finite t_intra of first layers 8hb..8hb+7 and last layer i
-//    ({DEV_INF, DEV_INF} if there is none), then the 8 values themselves: DEV_INF where the
-//    first layer is > i or >= K or the entry is +infinity}.
-// The array is padded by a few records so that the one-column-ahead loads may run past the
-// last column.
+// Table layout (built once per handle by repack_fast_kernel): for every (s-1, q, half-block hb)
+// a row of NP = ceil(K / 2) pair records, one per pair of neighbouring columns (last layers 2j
+// and 2j+1), of PAIR_INTS = 20 int32:
+//   [0..7]   t_intra of first layers 8hb..8hb+7 for last layer 2j      (DEV_INF where the first
+//   [8..15]  the same for last layer 2j+1                                layer is > the last or
+//   [16,17]  min, max over the finite entries of [0..7]                  >= K, or the entry is
+//   [18,19]  min, max over the finite entries of [8..15]                 +infinity)
+// ({DEV_INF, DEV_INF} if a half-column has no finite entry).  A wave walks its two rows front to
+// back, so its scalar loads stream through whole cache lines, and the folded form fetches a
+// batch (both columns of a pair) with one 16-dword and one 4-dword load.  The array is padded
+// by a few records so that the loads that run ahead may pass the last row's end.
 #pragma once
 #include "internal.hpp"
 
@@ -37,7 +40,8 @@ namespace alpa {
 
 typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-load path
 
-constexpr int HB_INTS = 10;
+constexpr int PAIR_INTS = 20;
+constexpr int fast_pairs_per_row(int K) { return (K + 1) / 2; }
 constexpr int END_SHAPES = 12;         // shapes covered by the early-stop table (3 registers)
 // Rows of an F layer in LDS beyond the KP first layers.  Three, not more: with 64 layers a
 // workgroup then takes 17152 + 3104 bytes of LDS and eight of them fit a compute unit.
@@ -53,12 +57,25 @@ struct HalfColumn {
     int32_t mn, mx;            // the half-block's min / max over finite entries
 };
 
-__device__ __forceinline__ void load_half(HalfColumn &h, cptr_t rec)
+// half-column of absolute column `col` from the row `row` of its (s, q, half-block)
+__device__ __forceinline__ void load_half(HalfColumn &h, cptr_t row, int col)
 {
-    h.mn = rec[0];
-    h.mx = rec[1];
+    const cptr_t pr = row + (size_t)(col >> 1) * PAIR_INTS;
+    const int odd = col & 1;
+    h.mn = pr[16 + 2 * odd];
+    h.mx = pr[17 + 2 * odd];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) h.t[u] = rec[2 + u];
+    for (int u = 0; u < 8; ++u) h.t[u] = pr[8 * odd + u];
+}
+// both half-columns of the pair record at `pr`
+__device__ __forceinline__ void load_pair(HalfColumn &x, HalfColumn &y, cptr_t pr)
+{
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x.t[u] = pr[u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) y.t[u] = pr[8 + u];
+    x.mn = pr[16]; x.mx = pr[17];
+    y.mn = pr[18]; y.mx = pr[19];
 }
 
 // Makes loaded values "used" here, so that the wait for them is placed before the next
@@ -304,7 +321,8 @@ void recurrence_fast_kernel(
     const int rowA = 8 * hbA, rowB = 8 * hbB;
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
-    constexpr int REC = (KP / 8) * HB_INTS;            // int32 per column record
+    const size_t ROW = (size_t)fast_pairs_per_row(p.K) * PAIR_INTS;   // int32 per (s, q, half-block) row
+    constexpr int NHB_ALL = KP / 8;
     constexpr int GW = end_group_cols(KP);             // columns per early-stop group
     const cptr_t recs = (cptr_t)recs_g;
     const cptr_t sizes = (cptr_t)sizes_g;
@@ -478,9 +496,8 @@ void recurrence_fast_kernel(
                 }
                 if (!FIRST && endA <= i0 && endB <= rowB) continue;  // nothing alive in reach
                 if (PASS_P) packed_any = true;
-                constexpr int STEP = REC;
-                const cptr_t rec0 = recs + (((size_t)(s - 1) * S + q) * K + i0) * REC;   // column i0
-                cptr_t pA = rec0 + hbA * HB_INTS, pB = rec0 + hbB * HB_INTS;
+                const cptr_t rowsq = recs + ((size_t)(s - 1) * S + q) * NHB_ALL * ROW;
+                const cptr_t pA = rowsq + hbA * ROW, pB = rowsq + hbB * ROW;    // the wave's two rows
                 const int ncol = i_hi - i0 + 1;                // columns of this wave
                 HalfColumn hA, hB;
                 int32_t G[NC];
@@ -490,9 +507,9 @@ void recurrence_fast_kernel(
                     for (int e = 0; e < NC; ++e)
                         G[e] = ((WIDE ? WAVE * e : 0) + gl + 1 == a) ? 0 : DEV_INF;
                     int i = i0;
-                    for (int x = 0; x < ncol; ++x, pA += STEP, pB += STEP, ++i) {
-                        load_half(hA, pA);
-                        load_half(hB, pB);
+                    for (int x = 0; x < ncol; ++x, ++i) {
+                        load_half(hA, pA, i);
+                        load_half(hB, pB, i);
                         if constexpr (GROUPED) {
                             relax8g<COUNT>(acc[0], 0, hA.t, hA.mn, hA.mx, G[0], c_lo, c[0], c_lane, n_blocks);
                             if (i >= rowB)
@@ -540,9 +557,10 @@ void recurrence_fast_kernel(
                         else
                             relax8<NC, COUNT>(acc, off, h.t, mn, h.mx, G, c, n_blocks);
                     };
-                    // `count` columns from the one p / frow point at, one half-block (acc rows
-                    // off..off+7) only
-                    auto single = [&](int off, cptr_t p, const int32_t *frow, int count, auto mnf) {
+                    // `count` columns from column c0 (frow: its operand row) of the row `row`,
+                    // one half-block (acc rows off..off+7) only; folded: c0 is even
+                    auto single = [&](int off, cptr_t row, int c0, const int32_t *frow, int count, auto mnf) {
+                        cptr_t pp = row + (size_t)(c0 >> 1) * PAIR_INTS;   // folded: pair of column c0
                         auto rows = [&](int32_t (&dst)[NF], int col) {
 #pragma unroll
                             for (int e = 0; e < NF; ++e)
@@ -551,8 +569,12 @@ void recurrence_fast_kernel(
                         auto load2 = [&](Batch &b, int col) {
                             rows(b.fX, col);
                             rows(b.fY, col + 1);
-                            load_half(b.X, p + (size_t)col * STEP);
-                            load_half(b.Y, p + (size_t)(col + 1) * STEP);
+                            if constexpr (FOLD) {
+                                load_pair(b.X, b.Y, pp + (col >> 1) * PAIR_INTS);
+                            } else {
+                                load_half(b.X, row, c0 + col);
+                                load_half(b.Y, row, c0 + col + 1);
+                            }
                             fence_loads();
                         };
                         auto compute2 = [&](Batch &b) {
@@ -584,20 +606,22 @@ void recurrence_fast_kernel(
                                 settle2(b1);
                                 load2(b0, 4);
                                 compute2(b1);
-                                p += 4 * STEP;
+                                pp += 2 * PAIR_INTS;
+                                c0 += 4;
                                 frow += 4 * WAVE;
                             }
                             if (left >= 2) {
                                 settle2(b0);
                                 compute2(b0);
-                                p += 2 * STEP;
+                                pp += PAIR_INTS;
+                                c0 += 2;
                                 frow += 2 * WAVE;
                                 left -= 2;
                             }
                         }
                         if (left == 1) {
                             rows(b0.fX, 0);
-                            load_half(b0.X, p);
+                            load_half(b0.X, row, c0);
                             operands(b0.fX);
                             relax(off, b0.X, mnf(b0.X));
                         }
@@ -613,9 +637,8 @@ void recurrence_fast_kernel(
                         // changes with the shape, so the loops around are not split on it.)
                         const int cB0 = max(i0, rowB);
                         if (live) {
-                            single(0, pA, row_ptr(i0), max(0, min(i_hi + 1, endA) - i0), mnA);
-                            single(8, pB + (size_t)(cB0 - i0) * STEP, row_ptr(cB0),
-                                   max(0, min(i_hi + 1, endB) - cB0), mnB);
+                            single(0, pA, i0, row_ptr(i0), max(0, min(i_hi + 1, endA) - i0), mnA);
+                            single(8, pB, cB0, row_ptr(cB0), max(0, min(i_hi + 1, endB) - cB0), mnB);
                         }
                         return;
                     }
@@ -625,16 +648,16 @@ void recurrence_fast_kernel(
                     const int nAB = max(0, min(ncol - n1, stopAB - cAB));
                     const int cB = cAB + nAB;                          // B alone from here
                     const int nB = max(0, min(i_hi + 1, endB) - cB);
-                    single(0, pA, row_ptr(i0), max(0, min(n1, endA - i0)), mnA);
+                    single(0, pA, i0, row_ptr(i0), max(0, min(n1, endA - i0)), mnA);
                     {
-                        cptr_t p1 = pA + (size_t)n1 * STEP, p2 = pB + (size_t)n1 * STEP;
+                        int cc = cAB;                                  // column of the next batch
                         const int32_t *frow = row_ptr(cAB);
                         auto load_AB = [&](Batch &b, int col) {
 #pragma unroll
                             for (int e = 0; e < NF; ++e)
                                 b.fX[e] = frow[(WIDE && e == 1 ? wide_delta : e * ROWS * WAVE) + col * WAVE];
-                            load_half(b.X, p1 + (size_t)col * STEP);
-                            load_half(b.Y, p2 + (size_t)col * STEP);
+                            load_half(b.X, pA, cc + col);
+                            load_half(b.Y, pB, cc + col);
                             fence_loads();
                         };
                         auto compute_AB = [&](Batch &b) {
@@ -656,8 +679,7 @@ void recurrence_fast_kernel(
                                 settle_AB(b1);
                                 load_AB(b0, 2);
                                 compute_AB(b1);
-                                p1 += 2 * STEP;
-                                p2 += 2 * STEP;
+                                cc += 2;
                                 frow += 2 * WAVE;
                             }
                             if (left == 1) {
@@ -666,7 +688,7 @@ void recurrence_fast_kernel(
                             }
                         }
                     }
-                    single(8, pB + (size_t)(cB - i0) * STEP, row_ptr(cB), nB, mnB);
+                    single(8, pB, cB, row_ptr(cB), nB, mnB);
                 };
                 columns(PASS_PACKED);
                 }

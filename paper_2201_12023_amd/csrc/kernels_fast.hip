@@ -7,30 +7,33 @@ namespace alpa {
 __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int S, int KP,
                                    int32_t *__restrict__ recs)
 {
-    // one thread per (s, q, i, hb)
-    const int NHB = KP / 8;
-    const long long total = (long long)K * S * K * NHB;
+    // one thread per (s, q, hb, column pair j): the pair record of last layers 2j and 2j+1
+    const int NHB = KP / 8, NP = fast_pairs_per_row(K);
+    const long long total = (long long)K * S * NHB * NP;
     for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
          e += (long long)gridDim.x * blockDim.x) {
-        const int hb = (int)(e % NHB);
-        long long r = e / NHB;
-        const int i = (int)(r % K); r /= K;
+        const int j = (int)(e % NP);
+        long long r = e / NP;
+        const int hb = (int)(r % NHB); r /= NHB;
         const int q = (int)(r % S);
         const int s = (int)(r / S);
-        int32_t *rec = recs + ((((long long)s * S + q) * K + i) * NHB + hb) * HB_INTS;
-        int32_t mn = DEV_INF, mx = -1;
-        for (int u = 0; u < 8; ++u) {
-            const int k = 8 * hb + u;
-            int32_t v = DEV_INF;
-            if (k <= i && k < K) {
-                const int32_t t = table[(((long long)s * K + k) * K + i) * S + q];
-                if (t != INF_I32) v = t;
+        int32_t *rec = recs + e * PAIR_INTS;
+        for (int half = 0; half < 2; ++half) {
+            const int i = 2 * j + half;
+            int32_t mn = DEV_INF, mx = -1;
+            for (int u = 0; u < 8; ++u) {
+                const int k = 8 * hb + u;
+                int32_t v = DEV_INF;
+                if (i < K && k <= i && k < K) {
+                    const int32_t t = table[(((long long)s * K + k) * K + i) * S + q];
+                    if (t != INF_I32) v = t;
+                }
+                rec[8 * half + u] = v;
+                if (v < DEV_INF) { mn = min(mn, v); mx = max(mx, v); }
             }
-            rec[2 + u] = v;
-            if (v < DEV_INF) { mn = min(mn, v); mx = max(mx, v); }
+            rec[16 + 2 * half] = mn;
+            rec[17 + 2 * half] = (mx < 0) ? DEV_INF : mx;
         }
-        rec[0] = mn;
-        rec[1] = (mx < 0) ? DEV_INF : mx;
     }
 }
 
@@ -54,8 +57,9 @@ __global__ void repack_group_min_kernel(int K, int S, int KP, int SW, const int3
                                                        // kernel clamps candidates below DEV_INF)
         for (int j = END_GROUPS - 1; j >= 0; --j) {
             if (s1 < K)
-                for (int i = min(K, GW * j + GW) - 1; i >= GW * j; --i)
-                    run = min(run, recs[((((long long)s1 * S + q) * K + i) * NHB + hb) * HB_INTS]);
+                for (int i = min(K, GW * j + GW) - 1; i >= GW * j; --i)    // the half-column's min
+                    run = min(run, recs[((((long long)s1 * S + q) * NHB + hb) * fast_pairs_per_row(K) +
+                                         (i >> 1)) * PAIR_INTS + 16 + 2 * (i & 1)]);
             g[((q * NHB + hb) * END_GROUPS + j) * SW + s1] = run;
         }
     }
@@ -71,10 +75,10 @@ __global__ void repack_padding_kernel(int32_t *__restrict__ p, int n)
 hipError_t launch_repack_fast(hipStream_t st, const int32_t *table, int K, int D, int S, int KP,
                               int32_t *recs, int32_t *group_min)
 {
-    const int rec_ints = (KP / 8) * HB_INTS;
-    hipLaunchKernelGGL(repack_padding_kernel, dim3(8), dim3(256), 0, st,
-                       recs + (size_t)K * S * K * rec_ints, 32 * rec_ints);
-    long long total = (long long)K * K * S * (KP / 8);
+    const size_t real_ints = (size_t)K * S * (KP / 8) * fast_pairs_per_row(K) * PAIR_INTS;
+    hipLaunchKernelGGL(repack_padding_kernel, dim3(8), dim3(256), 0, st, recs + real_ints,
+                       (int)(fast_table_ints(K, S) - real_ints));
+    long long total = (long long)K * S * (KP / 8) * fast_pairs_per_row(K);
     int grid = (int)((total + 255) / 256);
     if (grid > 8192) grid = 8192;
     hipLaunchKernelGGL(repack_fast_kernel, dim3(grid), dim3(256), 0, st, table, K, S, KP, recs);
@@ -96,7 +100,8 @@ size_t fast_group_min_ints(int K, int D, int S)
 size_t fast_table_ints(int K, int S)
 {
     const int KP = 16 * ((K + 15) / 16);
-    return ((size_t)K * S * K + 32) * (size_t)((KP / 8) * HB_INTS);     // 32 records of padding
+    // the rows, and 64 pair records of padding
+    return ((size_t)K * S * (KP / 8) * fast_pairs_per_row(K) + 64) * (size_t)PAIR_INTS;
 }
 
 // nc = candidates per workgroup (1 or 2; meshes of more than 64 devices: always one, in the
