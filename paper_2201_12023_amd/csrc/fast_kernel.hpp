@@ -128,7 +128,7 @@ __device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)
 #pragma unroll
                 for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[e]) ? t[u] : DEV_INF;
             }
-            if (COUNT) ++n_blocks;
+            if (COUNT) n_blocks += 8;
             relax_update(acc[e], off, t, G[e]);
             // (the next candidate filters the same eight registers in place: the compiler puts
             // its selects between this candidate's sums and minima)
@@ -140,22 +140,31 @@ __device__ __forceinline__ void relax8(int32_t (*acc)[16], int off, int32_t (&t)
 // Two columns of one half-block in one go (single candidate): acc = min3(acc, tX + GX, tY + GY),
 // three vector instructions for two cell-updates per row instead of four.  Worth it where the
 // kernel is bound by vector issue, which the one-candidate instances are (seven waves per SIMD).
+// R < 8: only the first R first layers of the half-block (the others have no entry in these
+// columns: see the diagonal columns in the kernel).
+template <int R = 8>
 __device__ __forceinline__ void relax_update2(int32_t *acc, int off, const int32_t (&tX)[8], int32_t GX,
                                               const int32_t (&tY)[8], int32_t GY)
 {
 #pragma unroll
-    for (int h = 0; h < 8; h += 4) {               // four rows at a time: eight sums in flight
-        int32_t sx[4], sy[4];
+    for (int h = 0; h < R; h += 4) {               // four rows at a time: eight sums in flight
+        constexpr int N4 = 4;
+        int32_t sx[N4], sy[N4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { sx[u] = tX[h + u] + GX; sy[u] = tY[h + u] + GY; }
-        asm volatile("" : "+v"(sx[0]), "+v"(sx[1]), "+v"(sx[2]), "+v"(sx[3]), "+v"(sy[0]),
-                          "+v"(sy[1]), "+v"(sy[2]), "+v"(sy[3]));
+        for (int u = 0; u < N4; ++u)
+            if (h + u < R) { sx[u] = tX[h + u] + GX; sy[u] = tY[h + u] + GY; }
+        if (h + 4 <= R)
+            asm volatile("" : "+v"(sx[0]), "+v"(sx[1]), "+v"(sx[2]), "+v"(sx[3]), "+v"(sy[0]),
+                              "+v"(sy[1]), "+v"(sy[2]), "+v"(sy[3]));
+        else
+            asm volatile("" : "+v"(sx[0]), "+v"(sx[1]), "+v"(sy[0]), "+v"(sy[1]));
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc[off + h + u] = min(acc[off + h + u], min(sx[u], sy[u]));
+        for (int u = 0; u < N4; ++u)
+            if (h + u < R) acc[off + h + u] = min(acc[off + h + u], min(sx[u], sy[u]));
     }
 }
 
-template <bool COUNT>
+template <bool COUNT, int R = 8>
 __device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnX,
                                          int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mnY,
                                          int32_t mxY, int32_t GY, int32_t c, unsigned &n_blocks)
@@ -165,17 +174,18 @@ __device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8]
     // maximum above it too, so the filter turns it into all-infinite entries, which the
     // minimum ignores: no separate code for "only one of the two", whose extra exits cost the
     // common path several taken branches.
+    static_assert(R == 2 || R == 4 || R == 6 || R == 8, "rows of a diagonal batch");
     if (mnX <= c || mnY <= c) {
         if (mxX > c) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) tX[u] = (tX[u] <= c) ? tX[u] : DEV_INF;
+            for (int u = 0; u < R; ++u) tX[u] = (tX[u] <= c) ? tX[u] : DEV_INF;
         }
         if (mxY > c) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) tY[u] = (tY[u] <= c) ? tY[u] : DEV_INF;
+            for (int u = 0; u < R; ++u) tY[u] = (tY[u] <= c) ? tY[u] : DEV_INF;
         }
-        if (COUNT) n_blocks += (mnX <= c ? 1 : 0) + (mnY <= c ? 1 : 0);
-        relax_update2(acc, off, tX, GX, tY, GY);
+        if (COUNT) n_blocks += R * ((mnX <= c ? 1 : 0) + (mnY <= c ? 1 : 0));   // rows, see below
+        relax_update2<R>(acc, off, tX, GX, tY, GY);
     }
 }
 
@@ -200,7 +210,7 @@ __device__ __forceinline__ void relax8g(int32_t *acc, int off, int32_t (&t)[8], 
                                         unsigned &n_blocks)
 {
     if (mn <= c_hi) {
-        if (COUNT) ++n_blocks;
+        if (COUNT) n_blocks += 8;
         if (mx <= c_lo) relax_update(acc, off, t, G);
         else relax_update_lanes(acc, off, t, G, c_lane);
     }
@@ -213,7 +223,7 @@ __device__ __forceinline__ void relax8x2g(int32_t *acc, int off, int32_t (&tX)[8
                                           int32_t c_lane, unsigned &n_blocks)
 {
     if (mnX <= c_hi || mnY <= c_hi) {
-        if (COUNT) n_blocks += (mnX <= c_hi ? 1 : 0) + (mnY <= c_hi ? 1 : 0);
+        if (COUNT) n_blocks += 8 * ((mnX <= c_hi ? 1 : 0) + (mnY <= c_hi ? 1 : 0));
         if (mxX <= c_lo && mxY <= c_lo) {
             relax_update2(acc, off, tX, GX, tY, GY);
         } else {
@@ -248,7 +258,7 @@ __device__ __forceinline__ void relax8p(int32_t (&accP)[16], int off, int32_t (&
             for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[1]) ? t[u] : DEV_INF;
         }
         const int32_t G1 = (both || half1) ? GP : DEV_INF;
-        if (COUNT) ++n_blocks;
+        if (COUNT) n_blocks += 8;
         relax_update(accP, off, t, G1);
         if (!both) {
             asm volatile("" : "+s"(t[0]), "+s"(t[1]), "+s"(t[2]), "+s"(t[3]), "+s"(t[4]),
@@ -259,7 +269,7 @@ __device__ __forceinline__ void relax8p(int32_t (&accP)[16], int off, int32_t (&
 #pragma unroll
             for (int u = 0; u < 8; ++u) t[u] = (t[u] <= c[0]) ? t[u] : DEV_INF;
             const int32_t G0 = half1 ? DEV_INF : GP;
-            if (COUNT) ++n_blocks;
+            if (COUNT) n_blocks += 8;
             relax_update(accP, off, t, G0);
         }
     }
@@ -577,6 +587,14 @@ void recurrence_fast_kernel(
                             }
                             fence_loads();
                         };
+                        // the first eight columns of a half-block's own pass are its diagonal:
+                        // column 8hb + j has entries for the first layers 8hb .. 8hb + j only, so
+                        // the batch of columns j = 2b, 2b+1 needs the first 2b + 2 rows
+                        auto compute2_rows = [&](Batch &b, auto ROWS_T) {
+                            relax8x2<COUNT, decltype(ROWS_T)::value>(acc[0], off, b.X.t, mnf(b.X), b.X.mx,
+                                                                     b.fX[0], b.Y.t, mnf(b.Y), b.Y.mx,
+                                                                     b.fY[0], c[0], n_blocks);
+                        };
                         auto compute2 = [&](Batch &b) {
                             if constexpr (GROUPED) {
                                 relax8x2g<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
@@ -599,6 +617,26 @@ void recurrence_fast_kernel(
                         int left = count;
                         if (left >= 2) {
                             load2(b0, 0);
+                            if constexpr (FOLD && !GROUPED) {
+                                if (left >= 8) {           // (c0 is the half-block's first column)
+                                    settle2(b0);
+                                    load2(b1, 2);
+                                    compute2_rows(b0, std::integral_constant<int, 2>{});
+                                    settle2(b1);
+                                    load2(b0, 4);
+                                    compute2_rows(b1, std::integral_constant<int, 4>{});
+                                    settle2(b0);
+                                    load2(b1, 6);
+                                    compute2_rows(b0, std::integral_constant<int, 6>{});
+                                    settle2(b1);
+                                    load2(b0, 8);
+                                    compute2(b1);
+                                    pp += 4 * PAIR_INTS;
+                                    c0 += 8;
+                                    frow += 8 * WAVE;
+                                    left -= 8;
+                                }
+                            }
                             for (; left >= 4; left -= 4) {
                                 settle2(b0);
                                 load2(b1, 2);
@@ -797,7 +835,8 @@ void recurrence_fast_kernel(
         __syncthreads();                               // LDS is reused by the next group
     }
     // (the last lane: it takes part in every pass, also where the low lanes sit one out)
-    if (COUNT) atomicAdd(wave_relax, lane == WAVE - 1 ? n_blocks_total * 8ull : 0ull);
+    // n_blocks counts rows (64-lane add + minimum groups) of the updates executed
+    if (COUNT) atomicAdd(wave_relax, lane == WAVE - 1 ? n_blocks_total : 0ull);
 }
 
 // shape-axis wave groups of the single-candidate (plan) run: as many as 1024 threads allow
