@@ -22,12 +22,13 @@
 //
 // Table layout (built once per handle by repack_fast_kernel): for every (s-1, q, half-block hb)
 // a row of NP = ceil(K / 2) pair records, one per pair of neighbouring columns (last layers 2j
-// and 2j+1), of PAIR_INTS = 20 int32:
+// and 2j+1), of PAIR_INTS = 22 int32:
 //   [0..7]   t_intra of first layers 8hb..8hb+7 for last layer 2j      (DEV_INF where the first
 //   [8..15]  the same for last layer 2j+1                                layer is > the last or
-//   [16,17]  min, max over the finite entries of [0..7]                  >= K, or the entry is
-//   [18,19]  min, max over the finite entries of [8..15]                 +infinity)
-// ({DEV_INF, DEV_INF} if a half-column has no finite entry).  A wave walks its two rows front to
+//   [16,17]  min, max over the finite entries of [0..15]                 >= K, or the entry is
+//   [18,19]  max over the finite entries of [0..7], of [8..15]           +infinity)
+//   [20,21]  min over the finite entries of [0..7], of [8..15]
+// (DEV_INF for a minimum or maximum over nothing).  A wave walks its two rows front to
 // back, so its scalar loads stream through whole cache lines, and the folded form fetches a
 // batch (both columns of a pair) with one 16-dword and one 4-dword load.  The array is padded
 // by a few records so that the loads that run ahead may pass the last row's end.
@@ -40,7 +41,7 @@ namespace alpa {
 
 typedef const __attribute__((address_space(4))) int32_t *cptr_t;   // scalar-load path
 
-constexpr int PAIR_INTS = 20;
+constexpr int PAIR_INTS = 22;
 constexpr int fast_pairs_per_row(int K) { return (K + 1) / 2; }
 constexpr int END_SHAPES = 12;         // shapes covered by the early-stop table (3 registers)
 // Rows of an F layer in LDS beyond the KP first layers.  Three, not more: with 64 layers a
@@ -62,20 +63,21 @@ __device__ __forceinline__ void load_half(HalfColumn &h, cptr_t row, int col)
 {
     const cptr_t pr = row + (size_t)(col >> 1) * PAIR_INTS;
     const int odd = col & 1;
-    h.mn = pr[16 + 2 * odd];
-    h.mx = pr[17 + 2 * odd];
+    h.mn = pr[20 + odd];
+    h.mx = pr[18 + odd];
 #pragma unroll
     for (int u = 0; u < 8; ++u) h.t[u] = pr[8 * odd + u];
 }
-// both half-columns of the pair record at `pr`
+// both half-columns of the pair record at `pr`: x.mn / y.mn receive the PAIR's minimum and
+// maximum (what the folded update classifies a batch by), x.mx / y.mx the half-columns' maxima
 __device__ __forceinline__ void load_pair(HalfColumn &x, HalfColumn &y, cptr_t pr)
 {
 #pragma unroll
     for (int u = 0; u < 8; ++u) x.t[u] = pr[u];
 #pragma unroll
     for (int u = 0; u < 8; ++u) y.t[u] = pr[8 + u];
-    x.mn = pr[16]; x.mx = pr[17];
-    y.mn = pr[18]; y.mx = pr[19];
+    x.mn = pr[16]; y.mn = pr[17];
+    x.mx = pr[18]; y.mx = pr[19];
 }
 
 // Makes loaded values "used" here, so that the wait for them is placed before the next
@@ -165,26 +167,29 @@ __device__ __forceinline__ void relax_update2(int32_t *acc, int off, const int32
 }
 
 template <bool COUNT, int R = 8>
-__device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnX,
-                                         int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mnY,
+__device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnXY,
+                                         int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mxXY,
                                          int32_t mxY, int32_t GY, int32_t c, unsigned &n_blocks)
 {
-    // One path: skipped if neither half-column has an entry for the candidate, else both are
-    // filtered where needed and folded.  A half-column with nothing for the candidate has its
-    // maximum above it too, so the filter turns it into all-infinite entries, which the
-    // minimum ignores: no separate code for "only one of the two", whose extra exits cost the
-    // common path several taken branches.
+    // One path: skipped if the pair has no entry for the candidate (its minimum mnXY is above
+    // it), taken as it is if every entry passes (its maximum mxXY does), else each half-column
+    // is filtered where its own maximum exceeds the candidate.  A half-column with nothing for
+    // the candidate has its maximum above it too, so the filter turns it into all-infinite
+    // entries, which the minimum ignores: no separate code for "only one of the two", whose
+    // extra exits cost the common path several taken branches.
     static_assert(R == 2 || R == 4 || R == 6 || R == 8, "rows of a diagonal batch");
-    if (mnX <= c || mnY <= c) {
-        if (mxX > c) {
+    if (mnXY <= c) {
+        if (mxXY > c) {
+            if (mxX > c) {
 #pragma unroll
-            for (int u = 0; u < R; ++u) tX[u] = (tX[u] <= c) ? tX[u] : DEV_INF;
-        }
-        if (mxY > c) {
+                for (int u = 0; u < R; ++u) tX[u] = (tX[u] <= c) ? tX[u] : DEV_INF;
+            }
+            if (mxY > c) {
 #pragma unroll
-            for (int u = 0; u < R; ++u) tY[u] = (tY[u] <= c) ? tY[u] : DEV_INF;
+                for (int u = 0; u < R; ++u) tY[u] = (tY[u] <= c) ? tY[u] : DEV_INF;
+            }
         }
-        if (COUNT) n_blocks += R * ((mnX <= c ? 1 : 0) + (mnY <= c ? 1 : 0));   // rows, see below
+        if (COUNT) n_blocks += 2 * R;              // rows; a pair counts as two half-columns
         relax_update2<R>(acc, off, tX, GX, tY, GY);
     }
 }
@@ -217,18 +222,18 @@ __device__ __forceinline__ void relax8g(int32_t *acc, int off, int32_t (&t)[8], 
 }
 
 template <bool COUNT>
-__device__ __forceinline__ void relax8x2g(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnX,
-                                          int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mnY,
-                                          int32_t mxY, int32_t GY, int32_t c_lo, int32_t c_hi,
-                                          int32_t c_lane, unsigned &n_blocks)
+__device__ __forceinline__ void relax8x2g(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnXY,
+                                          int32_t GX, int32_t (&tY)[8], int32_t mxXY, int32_t GY,
+                                          int32_t c_lo, int32_t c_hi, int32_t c_lane,
+                                          unsigned &n_blocks)
 {
-    if (mnX <= c_hi || mnY <= c_hi) {
-        if (COUNT) n_blocks += 8 * ((mnX <= c_hi ? 1 : 0) + (mnY <= c_hi ? 1 : 0));
-        if (mxX <= c_lo && mxY <= c_lo) {
+    // mnXY / mxXY: minimum and maximum over the finite entries of the pair
+    if (mnXY <= c_hi) {
+        if (COUNT) n_blocks += 16;
+        if (mxXY <= c_lo) {
             relax_update2(acc, off, tX, GX, tY, GY);
         } else {
-            // an entry above the lane's candidate (all of them in a half-column that has
-            // nothing even for c_hi) turns into +infinity for that lane
+            // an entry above the lane's candidate turns into +infinity for that lane
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int32_t sx = (tX[u] <= c_lane) ? tX[u] + GX : DEV_INF;
@@ -592,17 +597,17 @@ void recurrence_fast_kernel(
                         // the batch of columns j = 2b, 2b+1 needs the first 2b + 2 rows
                         auto compute2_rows = [&](Batch &b, auto ROWS_T) {
                             relax8x2<COUNT, decltype(ROWS_T)::value>(acc[0], off, b.X.t, mnf(b.X), b.X.mx,
-                                                                     b.fX[0], b.Y.t, mnf(b.Y), b.Y.mx,
+                                                                     b.fX[0], b.Y.t, b.Y.mn, b.Y.mx,
                                                                      b.fY[0], c[0], n_blocks);
                         };
                         auto compute2 = [&](Batch &b) {
                             if constexpr (GROUPED) {
-                                relax8x2g<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
-                                                 mnf(b.Y), b.Y.mx, b.fY[0], c_lo, c[0], c_lane, n_blocks);
+                                relax8x2g<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.fX[0], b.Y.t, b.Y.mn,
+                                                 b.fY[0], c_lo, c[0], c_lane, n_blocks);
                             } else if constexpr (FOLD) {
                                 // (runs with only the lanes that have an operand switched on)
                                 relax8x2<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
-                                                mnf(b.Y), b.Y.mx, b.fY[0], c[0], n_blocks);
+                                                b.Y.mn, b.Y.mx, b.fY[0], c[0], n_blocks);
                             } else {
                                 operands(b.fX);
                                 relax(off, b.X, mnf(b.X));
@@ -635,6 +640,25 @@ void recurrence_fast_kernel(
                                     c0 += 8;
                                     frow += 8 * WAVE;
                                     left -= 8;
+                                }
+                            }
+                            if constexpr (FOLD && !GROUPED) {
+                                for (; left >= 8; left -= 8) {   // (loop control once per four batches)
+                                    settle2(b0);
+                                    load2(b1, 2);
+                                    compute2(b0);
+                                    settle2(b1);
+                                    load2(b0, 4);
+                                    compute2(b1);
+                                    settle2(b0);
+                                    load2(b1, 6);
+                                    compute2(b0);
+                                    settle2(b1);
+                                    load2(b0, 8);
+                                    compute2(b1);
+                                    pp += 4 * PAIR_INTS;
+                                    c0 += 8;
+                                    frow += 8 * WAVE;
                                 }
                             }
                             for (; left >= 4; left -= 4) {

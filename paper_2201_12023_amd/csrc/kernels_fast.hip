@@ -18,6 +18,7 @@ __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int
         const int q = (int)(r % S);
         const int s = (int)(r / S);
         int32_t *rec = recs + e * PAIR_INTS;
+        int32_t mn2 = DEV_INF, mx2 = -1;
         for (int half = 0; half < 2; ++half) {
             const int i = 2 * j + half;
             int32_t mn = DEV_INF, mx = -1;
@@ -31,9 +32,13 @@ __global__ void repack_fast_kernel(const int32_t *__restrict__ table, int K, int
                 rec[8 * half + u] = v;
                 if (v < DEV_INF) { mn = min(mn, v); mx = max(mx, v); }
             }
-            rec[16 + 2 * half] = mn;
-            rec[17 + 2 * half] = (mx < 0) ? DEV_INF : mx;
+            rec[18 + half] = (mx < 0) ? DEV_INF : mx;
+            rec[20 + half] = mn;
+            mn2 = min(mn2, mn);
+            mx2 = max(mx2, mx);
         }
+        rec[16] = mn2;
+        rec[17] = (mx2 < 0) ? DEV_INF : mx2;
     }
 }
 
@@ -59,7 +64,7 @@ __global__ void repack_group_min_kernel(int K, int S, int KP, int SW, const int3
             if (s1 < K)
                 for (int i = min(K, GW * j + GW) - 1; i >= GW * j; --i)    // the half-column's min
                     run = min(run, recs[((((long long)s1 * S + q) * NHB + hb) * fast_pairs_per_row(K) +
-                                         (i >> 1)) * PAIR_INTS + 16 + 2 * (i & 1)]);
+                                         (i >> 1)) * PAIR_INTS + 20 + (i & 1)]);
             g[((q * NHB + hb) * END_GROUPS + j) * SW + s1] = run;
         }
     }
