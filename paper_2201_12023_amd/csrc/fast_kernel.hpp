@@ -464,6 +464,16 @@ void recurrence_fast_kernel(
 #pragma unroll
         for (int e = 0; e < NC; ++e) { best[e] = DEV_INF; sbest[e] = 0; }
         unsigned n_blocks = 0;
+        // A launch that finds the records outside the L2 of its XCD (a first solve, or other
+        // kernels since the last one) pays for it: the workgroups of an XCD walk the records
+        // nearly in step at first, so a miss of one is a miss of all (workload 4: 4.2 instead of
+        // 3.3 ms).  During about the first ticket of every workgroup (decided from the ticket
+        // itself, so that the persistent loop is not peeled on it) each wave therefore touches,
+        // a layer ahead, the part of its rows that the next layer reads.  The loads land in one
+        // register that is never read; it stays reserved until the wait at the end of the ticket.
+        constexpr bool WARM = FOLD && NWK <= 4;
+        const bool warm_l2 = WARM && tk < (int)gridDim.x;
+        int32_t pf_touch = 0;
         // One layer of Eq. 3.  The first layer has a form of its own (the only finite operand is
         // F(0, K+1, 0) = 0) and is a separate instance of this body, in front of the loop over
         // the others: inside one loop the two forms meet at every shape, and the accumulators
@@ -483,6 +493,23 @@ void recurrence_fast_kernel(
 #pragma unroll
             for (int u = 0; u < 16; ++u) accP[u] = DEV_INF;
             int32_t c2[2] = {c[0], c[NC - 1]};
+            if constexpr (WARM) {
+                if (warm_l2 && s < s_top) {
+                    // layer s + 1 has columns up to K - s - 1; 128 bytes a lane, lanes 0..31 for
+                    // half-block A's row and 32..63 for B's (rows of 64 layers have 2816 bytes)
+                    const int hb = (lane & 32) ? hbB : hbA;
+                    const int lo = 4 * hb * PAIR_INTS;                     // pair of column 8 hb
+                    const int hi = (((K - s - 1) >> 1) + 1) * PAIR_INTS - 1;
+                    const int at = min(lo + 32 * (lane & 31), max(lo, hi));
+                    const int32_t *row = recs_g + ((size_t)s * S * NHB_ALL + hb) * ROW + at;
+                    for (int q = wi; q < S; q += WI) {
+                        const int a = __builtin_amdgcn_readlane(size_of_lane, q);
+                        if (a + s > D) continue;               // the shape leaves no device to s stages
+                        const int32_t *ptr = row + (size_t)q * NHB_ALL * ROW;
+                        asm volatile("global_load_dword %0, %1, off" : "+v"(pf_touch) : "v"(ptr) : "memory");
+                    }
+                }
+            }
             const int i_lo = FIRST ? K - 1 : 0;        // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
             const int i0 = max(i_lo, rowA);            // columns that reach half-block A
@@ -821,6 +848,7 @@ void recurrence_fast_kernel(
         };
         if (s_top >= 1) layer(1, std::true_type{});
         for (int s = 2; s <= s_top; ++s) layer(s, std::false_type{});
+        if constexpr (WARM) asm volatile("s_waitcnt vmcnt(0)" : "+v"(pf_touch) :: "memory");
         if constexpr (GROUPED) {
             // the lane of device count D in group grp holds F(s, first layer, all devices) of
             // candidate j0 + grp; every other lane (and every wave but wave 0) stores to the
