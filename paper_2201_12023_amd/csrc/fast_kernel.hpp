@@ -61,7 +61,7 @@ struct HalfColumn {
 // half-column of absolute column `col` from the row `row` of its (s, q, half-block)
 __device__ __forceinline__ void load_half(HalfColumn &h, cptr_t row, int col)
 {
-    const cptr_t pr = row + (size_t)(col >> 1) * PAIR_INTS;
+    const cptr_t pr = row + (uint32_t)(col >> 1) * PAIR_INTS;
     const int odd = col & 1;
     h.mn = pr[20 + odd];
     h.mx = pr[18 + odd];
@@ -336,7 +336,9 @@ void recurrence_fast_kernel(
     const int rowA = 8 * hbA, rowB = 8 * hbB;
     const int K = p.K, D = p.D, S = p.S;
     const int LS = (K + 2) * (D + 1);
-    const size_t ROW = (size_t)fast_pairs_per_row(p.K) * PAIR_INTS;   // int32 per (s, q, half-block) row
+    // int32 per (s, q, half-block) row; the whole array stays below 2^31 int32 (128 layers, 64
+    // shapes: 1.8e8), so positions in it are 32-bit and only the pointer sum is 64-bit
+    const uint32_t ROW = (uint32_t)fast_pairs_per_row(p.K) * PAIR_INTS;
     constexpr int NHB_ALL = KP / 8;
     constexpr int GW = end_group_cols(KP);             // columns per early-stop group
     const cptr_t recs = (cptr_t)recs_g;
@@ -501,15 +503,21 @@ void recurrence_fast_kernel(
                     const int lo = 4 * hb * PAIR_INTS;                     // pair of column 8 hb
                     const int hi = (((K - s - 1) >> 1) + 1) * PAIR_INTS - 1;
                     const int at = min(lo + 32 * (lane & 31), max(lo, hi));
-                    const int32_t *row = recs_g + ((size_t)s * S * NHB_ALL + hb) * ROW + at;
+                    const int32_t *row = recs_g + (((uint32_t)s * S * NHB_ALL + hb) * ROW + at);
                     for (int q = wi; q < S; q += WI) {
                         const int a = __builtin_amdgcn_readlane(size_of_lane, q);
                         if (a + s > D) continue;               // the shape leaves no device to s stages
-                        const int32_t *ptr = row + (size_t)q * NHB_ALL * ROW;
+                        const int32_t *ptr = row + (uint32_t)q * NHB_ALL * ROW;
                         asm volatile("global_load_dword %0, %1, off" : "+v"(pf_touch) : "v"(ptr) : "memory");
                     }
                 }
             }
+            // the layer's early-stop counts, those of shape q in lane q (one LDS read per layer
+            // instead of one per shape); shapes beyond the table get "all eight groups".  (A
+            // select, not a branch on the lane id: see the ticket comment.)
+            const int32_t ends_word =
+                sh_ends[(wid * (END_SHAPES / 4) + min(lane >> 2, END_SHAPES / 4 - 1)) * SW + s - 1];
+            const int32_t ends_of_lane = lane < END_SHAPES ? (ends_word >> (8 * (lane & 3))) & 0xff : 0x88;
             const int i_lo = FIRST ? K - 1 : 0;        // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
             const int i0 = max(i_lo, rowA);            // columns that reach half-block A
@@ -529,17 +537,14 @@ void recurrence_fast_kernel(
                 // packed when every device count the shape can still serve is in the window
                 if ((PACK && !FIRST && a + s - 2 >= pk_base) != PASS_P) continue;
                 // first column group without anything for the largest candidate, per half-block
-                int endA = K, endB = K;
-                if (q < END_SHAPES) {
-                    const int bits = __builtin_amdgcn_readfirstlane(
-                        sh_ends[(wid * (END_SHAPES / 4) + (q >> 2)) * SW + s - 1]) >> (8 * (q & 3));
-                    endA = needA ? GW * (bits & 15) : 0;
-                    endB = needB ? GW * ((bits >> 4) & 15) : 0;
-                }
+                const int bits = __builtin_amdgcn_readlane(ends_of_lane, q);
+                const int endA = needA ? GW * (bits & 15) : 0;
+                const int endB = needB ? GW * ((bits >> 4) & 15) : 0;
                 if (!FIRST && endA <= i0 && endB <= rowB) continue;  // nothing alive in reach
                 if (PASS_P) packed_any = true;
-                const cptr_t rowsq = recs + ((size_t)(s - 1) * S + q) * NHB_ALL * ROW;
-                const cptr_t pA = rowsq + hbA * ROW, pB = rowsq + hbB * ROW;    // the wave's two rows
+                const uint32_t rowsq = ((uint32_t)(s - 1) * S + q) * NHB_ALL * ROW;
+                const cptr_t pA = recs + (rowsq + hbA * ROW);                   // the wave's two rows
+                const cptr_t pB = recs + (rowsq + hbB * ROW);
                 const int ncol = i_hi - i0 + 1;                // columns of this wave
                 HalfColumn hA, hB;
                 int32_t G[NC];
@@ -602,7 +607,7 @@ void recurrence_fast_kernel(
                     // `count` columns from column c0 (frow: its operand row) of the row `row`,
                     // one half-block (acc rows off..off+7) only; folded: c0 is even
                     auto single = [&](int off, cptr_t row, int c0, const int32_t *frow, int count, auto mnf) {
-                        cptr_t pp = row + (size_t)(c0 >> 1) * PAIR_INTS;   // folded: pair of column c0
+                        cptr_t pp = row + (uint32_t)(c0 >> 1) * PAIR_INTS; // folded: pair of column c0
                         auto rows = [&](int32_t (&dst)[NF], int col) {
 #pragma unroll
                             for (int e = 0; e < NF; ++e)
