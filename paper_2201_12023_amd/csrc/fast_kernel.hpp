@@ -312,6 +312,7 @@ void recurrence_fast_kernel(
     int32_t *__restrict__ F_all, const int32_t *__restrict__ s_top_p,
     const int32_t *__restrict__ group_min, int group_dp)
 {
+    static_assert((WI & (WI - 1)) == 0, "wave groups along the shape axis: a power of two");
     static_assert(!DUMP || NC == 1, "layer dump is for a single candidate");
     static_assert(!WIDE || (NC == 2 && WI == 1 && !DUMP), "two windows use the two-candidate layout");
     static_assert(!GROUPED || (NC == 1 && WI == 1 && !DUMP && !WIDE), "lane groups: one-candidate form");
@@ -521,6 +522,22 @@ void recurrence_fast_kernel(
             const int i_lo = FIRST ? K - 1 : 0;        // 0-based last layer
             const int i_hi = K - s;                    // at least s-1 layers must remain
             const int i0 = max(i_lo, rowA);            // columns that reach half-block A
+            // Which shapes this wave has work for in this layer, decided for all of them at once
+            // (lane q for shape q): the shape leaves a device to each of the s - 1 stages behind,
+            // the wave has columns at all, and the largest candidate still finds an entry in
+            // reach of one of its half-blocks.  The shape loop then walks the set bits.
+            const int32_t endA_l = needA ? GW * (ends_of_lane & 15) : 0;
+            const int32_t endB_l = needB ? GW * ((ends_of_lane >> 4) & 15) : 0;
+            const bool alive_l = lane < S && (lane & (WI - 1)) == wi && size_of_lane + s - 1 <= D &&
+                                 i0 <= i_hi && (FIRST || !(endA_l <= i0 && endB_l <= rowB));
+            // packed (two-candidate form) when every device count the shape can still serve is
+            // in the window
+            const bool packed_l = PACK && !FIRST && size_of_lane + s - 2 >= pk_base;
+            // folded form: the column counts of the two half-block passes, A's in bits 0..7 and
+            // B's in bits 8..15
+            const int cB0 = max(i0, rowB);
+            const int32_t counts_l = max(0, min(i_hi + 1, endA_l) - i0) |
+                                     (max(0, min(i_hi + 1, endB_l) - cB0) << 8);
             if (WI > 1) {
                 for (int x = tid; x < NC * ROWS * WAVE; x += NT) Fnext[x] = DEV_INF;
             }
@@ -530,17 +547,20 @@ void recurrence_fast_kernel(
             // of live accumulators, and with it the register traffic between them, small).
             auto shapes_pass = [&](auto PASS_PACKED) {
             constexpr bool PASS_P = decltype(PASS_PACKED)::value;
-            for (int q = wi; q < S; q += WI) {          // wave group wi takes every WI-th shape
+            // (wave group wi takes every WI-th shape)
+            unsigned long long todo = __ballot(alive_l && packed_l == PASS_P);
+            while (todo) {
+                const int q = __builtin_ctzll(todo);
+                todo &= todo - 1;
                 const int a = __builtin_amdgcn_readlane(size_of_lane, q);
-                if (a + s - 1 > D) continue;           // fewer than s-1 devices would remain
-                if (i0 > i_hi) continue;
-                // packed when every device count the shape can still serve is in the window
-                if ((PACK && !FIRST && a + s - 2 >= pk_base) != PASS_P) continue;
                 // first column group without anything for the largest candidate, per half-block
-                const int bits = __builtin_amdgcn_readlane(ends_of_lane, q);
-                const int endA = needA ? GW * (bits & 15) : 0;
-                const int endB = needB ? GW * ((bits >> 4) & 15) : 0;
-                if (!FIRST && endA <= i0 && endB <= rowB) continue;  // nothing alive in reach
+                // (the folded form takes its column counts from counts_l instead)
+                int endA = 0, endB = 0;
+                if constexpr (!FOLD) {
+                    const int bits = __builtin_amdgcn_readlane(ends_of_lane, q);
+                    endA = needA ? GW * (bits & 15) : 0;
+                    endB = needB ? GW * ((bits >> 4) & 15) : 0;
+                }
                 if (PASS_P) packed_any = true;
                 const uint32_t rowsq = ((uint32_t)(s - 1) * S + q) * NHB_ALL * ROW;
                 const cptr_t pA = recs + (rowsq + hbA * ROW);                   // the wave's two rows
@@ -729,10 +749,10 @@ void recurrence_fast_kernel(
                         // to update: they sit the pass out, which saves the select of the
                         // operand per column.  (Not a branch on the lane id alone: the set
                         // changes with the shape, so the loops around are not split on it.)
-                        const int cB0 = max(i0, rowB);
+                        const int counts = __builtin_amdgcn_readlane(counts_l, q);
                         if (live) {
-                            single(0, pA, i0, row_ptr(i0), max(0, min(i_hi + 1, endA) - i0), mnA);
-                            single(8, pB, cB0, row_ptr(cB0), max(0, min(i_hi + 1, endB) - cB0), mnB);
+                            single(0, pA, i0, row_ptr(i0), counts & 0xff, mnA);
+                            single(8, pB, cB0, row_ptr(cB0), counts >> 8, mnB);
                         }
                         return;
                     }
