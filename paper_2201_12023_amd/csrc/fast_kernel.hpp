@@ -166,10 +166,13 @@ __device__ __forceinline__ void relax_update2(int32_t *acc, int off, const int32
     }
 }
 
-template <bool COUNT, int R = 8>
-__device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8], int32_t mnXY,
-                                         int32_t mxX, int32_t GX, int32_t (&tY)[8], int32_t mxXY,
-                                         int32_t mxY, int32_t GY, int32_t c, unsigned &n_blocks)
+// NW = 2: the two windows of device counts of a mesh of 65..128 devices (one candidate, so one
+// filter; each window has its own accumulators and operands).
+template <bool COUNT, int R = 8, int NW = 1>
+__device__ __forceinline__ void relax8x2(int32_t (*acc)[16], int off, int32_t (&tX)[8], int32_t mnXY,
+                                         int32_t mxX, const int32_t (&GX)[NW], int32_t (&tY)[8],
+                                         int32_t mxXY, int32_t mxY, const int32_t (&GY)[NW], int32_t c,
+                                         unsigned &n_blocks)
 {
     // One path: skipped if the pair has no entry for the candidate (its minimum mnXY is above
     // it), taken as it is if every entry passes (its maximum mxXY does), else each half-column
@@ -189,8 +192,9 @@ __device__ __forceinline__ void relax8x2(int32_t *acc, int off, int32_t (&tX)[8]
                 for (int u = 0; u < R; ++u) tY[u] = (tY[u] <= c) ? tY[u] : DEV_INF;
             }
         }
-        if (COUNT) n_blocks += 2 * R;              // rows; a pair counts as two half-columns
-        relax_update2<R>(acc, off, tX, GX, tY, GY);
+        if (COUNT) n_blocks += 2 * R * NW;         // rows; a pair counts as two half-columns
+#pragma unroll
+        for (int w = 0; w < NW; ++w) relax_update2<R>(acc[w], off, tX, GX[w], tY, GY[w]);
     }
 }
 
@@ -351,7 +355,7 @@ void recurrence_fast_kernel(
     constexpr bool PACK = NC == 2 && WI == 1 && !DUMP && !WIDE;
     // one candidate per workgroup (batch and plan runs): two columns folded into one
     // three-operand minimum per row
-    constexpr bool FOLD = NC == 1 && !WIDE;
+    constexpr bool FOLD = NC == 1 || WIDE;
     const int pk_base = max(0, D - 32);
     const int pk_dl = pk_base + (lane & 31);
     const int pk_cand_off = (lane >> 5) * ROWS * WAVE;
@@ -647,19 +651,29 @@ void recurrence_fast_kernel(
                         // the first eight columns of a half-block's own pass are its diagonal:
                         // column 8hb + j has entries for the first layers 8hb .. 8hb + j only, so
                         // the batch of columns j = 2b, 2b+1 needs the first 2b + 2 rows
+                        // folded form: the operands as they come (only the lanes that have one
+                        // are switched on); with two windows the lanes below the shape's size
+                        // have one in window 1 only
+                        auto fold_operands = [&](Batch &b) {
+                            if constexpr (WIDE) {
+                                b.fX[0] = live ? b.fX[0] : DEV_INF;
+                                b.fY[0] = live ? b.fY[0] : DEV_INF;
+                            }
+                        };
                         auto compute2_rows = [&](Batch &b, auto ROWS_T) {
-                            relax8x2<COUNT, decltype(ROWS_T)::value>(acc[0], off, b.X.t, mnf(b.X), b.X.mx,
-                                                                     b.fX[0], b.Y.t, b.Y.mn, b.Y.mx,
-                                                                     b.fY[0], c[0], n_blocks);
+                            fold_operands(b);
+                            relax8x2<COUNT, decltype(ROWS_T)::value, NF>(acc, off, b.X.t, mnf(b.X), b.X.mx,
+                                                                         b.fX, b.Y.t, b.Y.mn, b.Y.mx,
+                                                                         b.fY, c[0], n_blocks);
                         };
                         auto compute2 = [&](Batch &b) {
                             if constexpr (GROUPED) {
                                 relax8x2g<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.fX[0], b.Y.t, b.Y.mn,
                                                  b.fY[0], c_lo, c[0], c_lane, n_blocks);
                             } else if constexpr (FOLD) {
-                                // (runs with only the lanes that have an operand switched on)
-                                relax8x2<COUNT>(acc[0], off, b.X.t, mnf(b.X), b.X.mx, b.fX[0], b.Y.t,
-                                                b.Y.mn, b.Y.mx, b.fY[0], c[0], n_blocks);
+                                fold_operands(b);
+                                relax8x2<COUNT, 8, NF>(acc, off, b.X.t, mnf(b.X), b.X.mx, b.fX, b.Y.t,
+                                                       b.Y.mn, b.Y.mx, b.fY, c[0], n_blocks);
                             } else {
                                 operands(b.fX);
                                 relax(off, b.X, mnf(b.X));
@@ -750,7 +764,7 @@ void recurrence_fast_kernel(
                         // operand per column.  (Not a branch on the lane id alone: the set
                         // changes with the shape, so the loops around are not split on it.)
                         const int counts = __builtin_amdgcn_readlane(counts_l, q);
-                        if (live) {
+                        if (WIDE ? live1 : live) {
                             single(0, pA, i0, row_ptr(i0), counts & 0xff, mnA);
                             single(8, pB, cB0, row_ptr(cB0), counts >> 8, mnB);
                         }
