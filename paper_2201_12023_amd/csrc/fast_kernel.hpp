@@ -14,11 +14,15 @@
 // row of 64 lanes per first layer.  For a fixed (last layer i, shape q) the operand
 // F(s-1, i+1, d - a_q) is one lane-shifted LDS row read, reused for all first layers of the
 // wave, and t_intra(k..i, q, s) is the same for all lanes: it is fetched with scalar loads
-// and used as the scalar operand of the add, so a cell-update costs one v_add and one v_min.
+// and used as the scalar operand of the add, so a cell-update costs one v_add and one v_min
+// (one and a half instructions where two neighbouring columns are folded into one
+// three-operand minimum: the one-candidate and the two-window forms).
 // The filter t_intra <= t_max is wave-uniform; it is resolved per half-block from its
 // precomputed min / max (skip, take unfiltered, or select per entry on the scalar unit).
 // Infinite entries need no filter: DEV_INF + anything >= DEV_INF and accumulators start at
-// DEV_INF.  Column loads (scalars and the LDS row) are issued one column ahead.
+// DEV_INF.  Column loads (scalars and the LDS row) are issued one batch of two columns ahead.
+// What is decided per shape (is there work for this wave in this layer, how many columns per
+// half-block) is computed for all shapes at once, lane q for shape q, once per layer.
 //
 // Table layout (built once per handle by repack_fast_kernel): for every (s-1, q, half-block hb)
 // a row of NP = ceil(K / 2) pair records, one per pair of neighbouring columns (last layers 2j
@@ -306,6 +310,10 @@ __device__ __forceinline__ bool can_skip_fast(const int64_t *chunk_min, int j, i
 // GROUPED (with NC = 1): meshes of up to 32 devices, 64 / DP candidates per workgroup (see
 // relax8g above).
 template <int NWK, int WI, int NC, bool DUMP, bool COUNT, bool WIDE = false, bool GROUPED = false>
+// (The batch instances of the one-candidate form are meant to run eight waves per SIMD, i.e.
+// in 64 vector registers.  Asking for eight here makes the compiler cut the scalar registers
+// to 80 as well and spill; asked for seven it stays within 64 of its own accord, which the
+// build step checks from the compiler's resource remarks.)
 __global__ __launch_bounds__(WAVE * NWK * WI)
 __attribute__((amdgpu_waves_per_eu((NC == 1 && WI == 1 && !DUMP && !WIDE && !GROUPED) ? 7 : 4)))
 void recurrence_fast_kernel(
