@@ -485,7 +485,9 @@ void recurrence_fast_kernel(
         // 3.3 ms).  During about the first ticket of every workgroup (decided from the ticket
         // itself, so that the persistent loop is not peeled on it) each wave therefore touches,
         // a layer ahead, the part of its rows that the next layer reads.  The loads land in one
-        // register that is never read; it stays reserved until the wait at the end of the ticket.
+        // register that is never read; it stays reserved until the wait at the end of the ticket
+        // (tied from asm to asm, so it keeps its place unless it is spilled: the build step
+        // refuses a recurrence kernel that spills, to scratch or to accumulation registers).
         constexpr bool WARM = FOLD && NWK <= 4;
         const bool warm_l2 = WARM && tk < (int)gridDim.x;
         int32_t pf_touch = 0;
