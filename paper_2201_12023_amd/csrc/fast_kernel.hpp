@@ -488,8 +488,10 @@ void recurrence_fast_kernel(
         // register that is never read; it stays reserved until the wait at the end of the ticket
         // (tied from asm to asm, so it keeps its place unless it is spilled: the build step
         // refuses a recurrence kernel that spills, to scratch or to accumulation registers).
-        constexpr bool WARM = FOLD && NWK <= 4;
-        const bool warm_l2 = WARM && tk < (int)gridDim.x;
+        constexpr bool WARM = FOLD;
+        // (more than 64 layers: the records of one candidate no longer fit the L2, every ticket
+        // streams them in, so every ticket touches ahead)
+        const bool warm_l2 = WARM && (NWK > 4 || tk < (int)gridDim.x);
         int32_t pf_touch = 0;
         // One layer of Eq. 3.  The first layer has a form of its own (the only finite operand is
         // F(0, K+1, 0) = 0) and is a separate instance of this body, in front of the loop over
@@ -514,16 +516,26 @@ void recurrence_fast_kernel(
                 if (warm_l2 && s < s_top) {
                     // layer s + 1 has columns up to K - s - 1; 128 bytes a lane, lanes 0..31 for
                     // half-block A's row and 32..63 for B's (rows of 64 layers have 2816 bytes)
-                    const int hb = (lane & 32) ? hbB : hbA;
-                    const int lo = 4 * hb * PAIR_INTS;                     // pair of column 8 hb
+                    // (more than 64 layers: rows of up to 5632 bytes, all 64 lanes for A's row
+                    // and a second load for B's)
+                    constexpr int LANES = NWK <= 4 ? 32 : WAVE;
                     const int hi = (((K - s - 1) >> 1) + 1) * PAIR_INTS - 1;
-                    const int at = min(lo + 32 * (lane & 31), max(lo, hi));
+                    const int hb = (NWK <= 4 && (lane & 32)) ? hbB : hbA;
+                    const int lo = 4 * hb * PAIR_INTS;                     // pair of column 8 hb
+                    const int at = min(lo + 32 * (lane & (LANES - 1)), max(lo, hi));
                     const int32_t *row = recs_g + (((uint32_t)s * S * NHB_ALL + hb) * ROW + at);
+                    const int loB = 4 * hbB * PAIR_INTS;
+                    const int atB = min(loB + 32 * lane, max(loB, hi));
+                    const int32_t *rowB2 = recs_g + (((uint32_t)s * S * NHB_ALL + hbB) * ROW + atB);
                     for (int q = wi; q < S; q += WI) {
                         const int a = __builtin_amdgcn_readlane(size_of_lane, q);
                         if (a + s > D) continue;               // the shape leaves no device to s stages
                         const int32_t *ptr = row + (uint32_t)q * NHB_ALL * ROW;
                         asm volatile("global_load_dword %0, %1, off" : "+v"(pf_touch) : "v"(ptr) : "memory");
+                        if constexpr (NWK > 4) {
+                            const int32_t *ptrB = rowB2 + (uint32_t)q * NHB_ALL * ROW;
+                            asm volatile("global_load_dword %0, %1, off" : "+v"(pf_touch) : "v"(ptrB) : "memory");
+                        }
                     }
                 }
             }
